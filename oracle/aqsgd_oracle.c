@@ -1,0 +1,403 @@
+/*
+ * CPU oracle for the AQ-SGD stage-boundary codec.
+ *
+ * TEST INFRASTRUCTURE ONLY.  Plain, slow, scalar C that follows the method
+ * step by step so it can be read against the paper.  It shares no code with
+ * the HIP library and must never be called from the product path; only the
+ * tests, the smoke check and the CPU-baseline leg of the benchmark use it.
+ *
+ * What it computes
+ *   - Sender and receiver sides of the forward message (Algorithm 2, "on
+ *     network a" / "on network b"; Algorithm 1's update of m):
+ *         delta   = a(xi) - m(xi)
+ *         Delta m = Q(delta)
+ *         m(xi)  <- m(xi) + Delta m          (identically on both machines)
+ *   - The backward message Q(grad) and its reconstruction (Algorithm 1,
+ *     the two comment lines about Machine b sending Q(grad)).
+ *   - Q itself: Section 4.1 ("normalizes a given vector into [-1,1] and
+ *     quantize each number into a b-bit integer by uniformly partitioning
+ *     [-1,1]"), with stochastic rounding as an option because Theorem 3.1
+ *     asks for an unbiased Q (its footnote rounds "stochastically").
+ *
+ * Readings taken where the paper leaves room (each is also listed in the
+ * design notes of this repository):
+ *   - the normaliser is the max-abs of a group of G consecutive elements;
+ *   - the 2^b levels are equally spaced points on [-s, s], both ends included
+ *     (spacing 2s/(2^b-1)), so the nearest-rounding error is <= s/(2^b-1);
+ *   - nearest rounding resolves ties upwards (floor(x + 1/2)) so that both
+ *     rounding modes are floor(x + r) with r = 1/2 or r ~ U[0,1);
+ *   - m starts at zero, so the first visit of a sample is direct quantisation;
+ *   - a group whose max-abs is below 2^-120 is sent as scale 0 / codes 0;
+ *   - m is kept in the activation's own dtype; the sum m + Delta m is formed
+ *     in binary32 and rounded to nearest-even once when stored;
+ *   - random numbers: Philox4x32-10 (Salmon et al., SC'11), counter = index
+ *     of the 4-element block within the call, key = the call's seed.
+ *
+ * Arithmetic: IEEE-754 binary32, round-to-nearest-even, one rounding per
+ * written operation, no contraction into FMA, subnormals kept.  Build with
+ *     gcc -O2 -std=c11 -ffp-contract=off -fno-fast-math
+ *
+ * Parity pins (tests/test_oracle_*.py): half/bfloat conversions against
+ * numpy/torch; Philox against the published known-answer vectors; the bit
+ * stream against Python big-integer arithmetic; the level decision against
+ * exact rational arithmetic; the hand-worked two-visit example; the paper's
+ * invariants (first visit = direct quantisation, replica identity, error
+ * bound, unbiasedness, contraction, message size).  No function here is
+ * "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORACLE_F32 = 0, ORACLE_F16 = 1, ORACLE_BF16 = 2 };
+enum { ORACLE_NEAREST = 0, ORACLE_STOCHASTIC = 1 };
+
+/* ------------------------------------------------------------------ */
+/* Storage formats, written from the IEEE-754 definitions.             */
+/* ------------------------------------------------------------------ */
+static uint32_t f32_bits(float x) { uint32_t u; memcpy(&u, &x, 4); return u; }
+static float bits_f32(uint32_t u) { float x; memcpy(&x, &u, 4); return x; }
+
+/* v / 2^shift rounded to the nearest integer, ties to the even one. */
+static uint64_t rne_shift(uint64_t v, int shift)
+{
+    if (shift <= 0) return v << (-shift);
+    if (shift > 62) return 0;
+    uint64_t kept = v >> shift;
+    uint64_t rest = v & ((1ull << shift) - 1);
+    uint64_t half = 1ull << (shift - 1);
+    if (rest > half || (rest == half && (kept & 1))) kept += 1;
+    return kept;
+}
+
+float aqsgd_oracle_half_to_float(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) << 31;
+    int exp = (h >> 10) & 0x1f;
+    uint32_t man = h & 0x3ff;
+    if (exp == 0) {                      /* zero or subnormal: man * 2^-24 */
+        float mag = (float)man * 0x1p-24f;
+        return bits_f32(sign | f32_bits(mag));
+    }
+    if (exp == 31)                       /* inf / nan */
+        return bits_f32(sign | 0x7f800000u | (man << 13));
+    return bits_f32(sign | ((uint32_t)(exp - 15 + 127) << 23) | (man << 13));
+}
+
+uint16_t aqsgd_oracle_float_to_half(float x)
+{
+    uint32_t u = f32_bits(x);
+    uint16_t sign = (uint16_t)((u >> 16) & 0x8000);
+    int bexp = (u >> 23) & 0xff;
+    uint32_t frac = u & 0x7fffff;
+    if (bexp == 0xff)                    /* inf / nan */
+        return (uint16_t)(sign | 0x7c00 | (frac ? (0x200 | (frac >> 13)) : 0));
+    if (bexp == 0) return sign;          /* |x| < 2^-126: far below half's range */
+    int e = bexp - 127;                  /* |x| = sig * 2^(e-23), sig in [2^23, 2^24) */
+    uint64_t sig = frac | 0x800000u;
+    uint32_t mag;
+    if (e >= -14) {
+        /* normal half: 11 significant bits */
+        uint64_t m = rne_shift(sig, 13);             /* in [2^10, 2^11] */
+        mag = ((uint32_t)(e + 15) << 10) + (uint32_t)(m - 1024);
+        if (mag >= 0x7c00) mag = 0x7c00;             /* overflow to infinity */
+    } else {
+        /* subnormal half: integer multiple of 2^-24 */
+        mag = (uint32_t)rne_shift(sig, 13 + (-14 - e));  /* in [0, 2^10] */
+    }
+    return (uint16_t)(sign | mag);
+}
+
+float aqsgd_oracle_bf16_to_float(uint16_t b) { return bits_f32((uint32_t)b << 16); }
+
+uint16_t aqsgd_oracle_float_to_bf16(float x)
+{
+    uint32_t u = f32_bits(x);
+    uint32_t sign = u & 0x80000000u, mag = u & 0x7fffffffu;
+    if (mag > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);   /* nan */
+    /* bfloat16 is binary32 cut to its top 16 bits; both formats are monotone
+       in their magnitude bits, so rounding the integer rounds the value. */
+    return (uint16_t)((sign >> 16) | (uint32_t)rne_shift(mag, 16));
+}
+
+static float load_elem(const void* p, int64_t idx, int dtype)
+{
+    switch (dtype) {
+    case ORACLE_F16:  return aqsgd_oracle_half_to_float(((const uint16_t*)p)[idx]);
+    case ORACLE_BF16: return aqsgd_oracle_bf16_to_float(((const uint16_t*)p)[idx]);
+    default:          return ((const float*)p)[idx];
+    }
+}
+
+static void store_elem(void* p, int64_t idx, int dtype, float v)
+{
+    switch (dtype) {
+    case ORACLE_F16:  ((uint16_t*)p)[idx] = aqsgd_oracle_float_to_half(v); break;
+    case ORACLE_BF16: ((uint16_t*)p)[idx] = aqsgd_oracle_float_to_bf16(v); break;
+    default:          ((float*)p)[idx] = v; break;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random         */
+/* numbers: as easy as 1, 2, 3", SC'11).                               */
+/* ------------------------------------------------------------------ */
+void aqsgd_oracle_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2],
+                                uint32_t out[4])
+{
+    uint32_t c0 = ctr_in[0], c1 = ctr_in[1], c2 = ctr_in[2], c3 = ctr_in[3];
+    uint32_t k0 = key_in[0], k1 = key_in[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;               /* key schedule between rounds */
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* Uniform in [0,1) for element j of a call: 24 random bits, exact in binary32. */
+float aqsgd_oracle_uniform(uint64_t seed, uint64_t j)
+{
+    uint64_t block = j / 4;
+    uint32_t ctr[4] = { (uint32_t)block, (uint32_t)(block >> 32), 0u, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t w[4];
+    aqsgd_oracle_philox4x32_10(ctr, key, w);
+    return (float)(w[j % 4] >> 8) * 0x1p-24f;
+}
+
+/* ------------------------------------------------------------------ */
+/* b-bit integers on the wire: element j owns stream bits              */
+/* [j*b, j*b+b); stream bit k is bit (k mod 8) of byte k/8.            */
+/* ------------------------------------------------------------------ */
+void aqsgd_oracle_pack(const int32_t* q, int64_t count, int bits, uint8_t* bytes)
+{
+    memset(bytes, 0, (size_t)((count * bits + 7) / 8));
+    for (int64_t j = 0; j < count; ++j)
+        for (int k = 0; k < bits; ++k)
+            if ((q[j] >> k) & 1) {
+                int64_t pos = j * bits + k;
+                bytes[pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+}
+
+void aqsgd_oracle_unpack(const uint8_t* bytes, int64_t count, int bits, int32_t* q)
+{
+    for (int64_t j = 0; j < count; ++j) {
+        int32_t v = 0;
+        for (int k = 0; k < bits; ++k) {
+            int64_t pos = j * bits + k;
+            if ((bytes[pos / 8] >> (pos % 8)) & 1) v |= (1 << k);
+        }
+        q[j] = v;
+    }
+}
+
+/* ------------------------------------------------------------------ */
+/* The quantiser Q on one group (Section 4.1).                         */
+/*   d[0..G)  binary32 inputs                                          */
+/*   r[0..G)  rounding offsets: 1/2 everywhere for nearest rounding,   */
+/*            U[0,1) draws for stochastic rounding                     */
+/* Out: level indices q in [0, 2^b-1], transmitted scale, Q(d).        */
+/* ------------------------------------------------------------------ */
+static float half_levels(int bits) { return (float)((1 << bits) - 1) / 2.0f; }
+
+void aqsgd_oracle_quantize_group(const float* d, const float* r, int64_t G, int bits,
+                                 int32_t* q, float* scale_out, float* dhat)
+{
+    const int L = (1 << bits) - 1;       /* index of the top level */
+    const float hL = half_levels(bits);  /* 1.5, 3.5, 7.5, 127.5: exact */
+
+    float s = 0.0f;                      /* normaliser: max |d| over the group */
+    for (int64_t e = 0; e < G; ++e) {
+        float a = fabsf(d[e]);
+        if (a > s) s = a;
+    }
+    if (s < 0x1p-120f) {                 /* nothing to send */
+        for (int64_t e = 0; e < G; ++e) { q[e] = 0; dhat[e] = 0.0f; }
+        *scale_out = 0.0f;
+        return;
+    }
+    const float inv = hL / s;            /* maps [-s, s] onto [-hL, hL] */
+    const float step = s / hL;           /* spacing of the levels */
+    for (int64_t e = 0; e < G; ++e) {
+        float t = d[e] * inv;            /* normalised, in level units */
+        t = t + hL;                      /* levels sit at 0, 1, ..., L */
+        float y = t + r[e];
+        int32_t k = (int32_t)floorf(y);
+        if (k < 0) k = 0;
+        if (k > L) k = L;
+        q[e] = k;
+        dhat[e] = ((float)k - hL) * step;
+    }
+    *scale_out = s;
+}
+
+/* Q^-1 on one group, as the receiver computes it from (codes, scale). */
+void aqsgd_oracle_dequantize_group(const int32_t* q, float scale, int64_t G, int bits,
+                                   float* dhat)
+{
+    const float hL = half_levels(bits);
+    if (scale == 0.0f) {
+        for (int64_t e = 0; e < G; ++e) dhat[e] = 0.0f;
+        return;
+    }
+    const float step = scale / hL;
+    for (int64_t e = 0; e < G; ++e) dhat[e] = ((float)q[e] - hL) * step;
+}
+
+static void rounding_offsets(int rounding, uint64_t seed, int64_t j0, int64_t G, float* r)
+{
+    for (int64_t e = 0; e < G; ++e)
+        r[e] = (rounding == ORACLE_STOCHASTIC)
+                   ? aqsgd_oracle_uniform(seed, (uint64_t)(j0 + e)) : 0.5f;
+}
+
+static int check_shape(int dtype, int bits, int64_t group, int rounding,
+                       int64_t batch, int64_t n_per)
+{
+    if (dtype < 0 || dtype > 2) return -1;
+    if (!(bits == 2 || bits == 3 || bits == 4 || bits == 8)) return -2;
+    if (group <= 0 || n_per <= 0 || n_per % group) return -3;
+    if ((group * bits) % 8) return -3;
+    if (rounding != ORACLE_NEAREST && rounding != ORACLE_STOCHASTIC) return -4;
+    if (batch < 0) return -5;
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Sender: Delta m = Q(a - m); m <- m + Delta m; emit Delta m.         */
+/* act [batch, n_per]; ids[batch] select rows of m_buf [*, n_per].     */
+/* Groups tile the call tensor contiguously: group g covers flat       */
+/* elements [g*G, g*G+G), which never straddles two samples.           */
+/* ------------------------------------------------------------------ */
+int aqsgd_oracle_encode(int dtype, int bits, int64_t group, int rounding, uint64_t seed,
+                        int64_t batch, int64_t n_per, const void* act,
+                        const int64_t* ids, void* m_buf, uint8_t* codes, float* scales)
+{
+    int rc = check_shape(dtype, bits, group, rounding, batch, n_per);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    const int64_t n_groups = batch * groups_per_sample;
+#pragma omp parallel
+    {
+        float* d = malloc(sizeof(float) * group);
+        float* m_old = malloc(sizeof(float) * group);
+        float* r = malloc(sizeof(float) * group);
+        float* dhat = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t i = g / groups_per_sample;          /* sample in call */
+            const int64_t within = (g % groups_per_sample) * group;
+            const int64_t a0 = i * n_per + within;            /* = g * group */
+            const int64_t m0 = ids[i] * n_per + within;       /* row of m(xi) */
+            for (int64_t e = 0; e < group; ++e) {
+                m_old[e] = load_elem(m_buf, m0 + e, dtype);
+                d[e] = load_elem(act, a0 + e, dtype) - m_old[e];
+            }
+            rounding_offsets(rounding, seed, a0, group, r);
+            aqsgd_oracle_quantize_group(d, r, group, bits, q, &scales[g], dhat);
+            for (int64_t e = 0; e < group; ++e)
+                store_elem(m_buf, m0 + e, dtype, m_old[e] + dhat[e]);
+            aqsgd_oracle_pack(q, group, bits, codes + a0 * bits / 8);
+        }
+        free(d); free(m_old); free(r); free(dhat); free(q);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Receiver: m <- m + Delta m on its own replica; the updated m is the */
+/* activation the next stage consumes.                                 */
+/* ------------------------------------------------------------------ */
+int aqsgd_oracle_decode(int dtype, int bits, int64_t group, int64_t batch, int64_t n_per,
+                        const uint8_t* codes, const float* scales, const int64_t* ids,
+                        void* m_buf, void* out)
+{
+    int rc = check_shape(dtype, bits, group, ORACLE_NEAREST, batch, n_per);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    const int64_t n_groups = batch * groups_per_sample;
+#pragma omp parallel
+    {
+        float* dhat = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t i = g / groups_per_sample;
+            const int64_t within = (g % groups_per_sample) * group;
+            const int64_t a0 = i * n_per + within;
+            const int64_t m0 = ids[i] * n_per + within;
+            aqsgd_oracle_unpack(codes + a0 * bits / 8, group, bits, q);
+            aqsgd_oracle_dequantize_group(q, scales[g], group, bits, dhat);
+            for (int64_t e = 0; e < group; ++e) {
+                float m_new = load_elem(m_buf, m0 + e, dtype) + dhat[e];
+                store_elem(m_buf, m0 + e, dtype, m_new);
+                /* hand over exactly what was stored */
+                store_elem(out, a0 + e, dtype, load_elem(m_buf, m0 + e, dtype));
+            }
+        }
+        free(dhat); free(q);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Backward message: Q(grad) directly, no buffer.                      */
+/* ------------------------------------------------------------------ */
+int aqsgd_oracle_grad_quant(int dtype, int bits, int64_t group, int rounding, uint64_t seed,
+                            int64_t batch, int64_t n_per, const void* grad,
+                            uint8_t* codes, float* scales)
+{
+    int rc = check_shape(dtype, bits, group, rounding, batch, n_per);
+    if (rc) return rc;
+    const int64_t n_groups = batch * (n_per / group);
+#pragma omp parallel
+    {
+        float* d = malloc(sizeof(float) * group);
+        float* r = malloc(sizeof(float) * group);
+        float* dhat = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t a0 = g * group;
+            for (int64_t e = 0; e < group; ++e) d[e] = load_elem(grad, a0 + e, dtype);
+            rounding_offsets(rounding, seed, a0, group, r);
+            aqsgd_oracle_quantize_group(d, r, group, bits, q, &scales[g], dhat);
+            aqsgd_oracle_pack(q, group, bits, codes + a0 * bits / 8);
+        }
+        free(d); free(r); free(dhat); free(q);
+    }
+    return 0;
+}
+
+int aqsgd_oracle_grad_dequant(int dtype, int bits, int64_t group, int64_t batch,
+                              int64_t n_per, const uint8_t* codes, const float* scales,
+                              void* out)
+{
+    int rc = check_shape(dtype, bits, group, ORACLE_NEAREST, batch, n_per);
+    if (rc) return rc;
+    const int64_t n_groups = batch * (n_per / group);
+#pragma omp parallel
+    {
+        float* dhat = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t a0 = g * group;
+            aqsgd_oracle_unpack(codes + a0 * bits / 8, group, bits, q);
+            aqsgd_oracle_dequantize_group(q, scales[g], group, bits, dhat);
+            for (int64_t e = 0; e < group; ++e) store_elem(out, a0 + e, dtype, dhat[e]);
+        }
+        free(dhat); free(q);
+    }
+    return 0;
+}
