@@ -1,0 +1,147 @@
+/*
+ * aqsgd.h -- C ABI of the MI355X stage-boundary codec of AQ-SGD
+ * ("Fine-tuning Language Models over Slow Networks using Activation
+ * Quantization with Guarantees", NeurIPS 2022).
+ *
+ * Between two pipeline stages the method does not quantise the activation a(xi)
+ * of training sample xi itself, but its change against m(xi), the message the
+ * two stages exchanged the last time they saw xi, which both keep (Algorithm 1;
+ * Algorithm 2 is the two-machine view):
+ *
+ *     sender:    Delta m = Q(a(xi) - m(xi));  m(xi) <- m(xi) + Delta m;  send Delta m
+ *     receiver:  m(xi) <- m(xi) + Delta m;    the next stage consumes m(xi)
+ *     backward:  receiver sends Q(gradient w.r.t. the activation), directly
+ *
+ * Q (Section 4.1) normalises a group of G consecutive elements by its max-abs s
+ * and maps each onto one of 2^b equally spaced levels on [-s, s]; rounding is to
+ * nearest (ties upwards) or stochastic (unbiased, as Theorem 3.1 requires).
+ *
+ * General rules for every entry point
+ *   - Every data pointer is DEVICE memory on the current HIP device, owned by the
+ *     caller before, during and after the call; the library allocates nothing,
+ *     keeps no state between calls and may be called from several host threads.
+ *     The descriptor is HOST memory and is read before the call returns.
+ *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
+ *     the default stream) and return; results are valid once the stream reaches
+ *     that point.  Ordering between a sender's and a receiver's stream is the
+ *     caller's business (events).
+ *   - Tensors are dense, row-major.  act/grad/out are [batch, n_per]; m_buf is
+ *     [n_samples, n_per]; all in `dtype`.  Groups tile the flattened call tensor:
+ *     group g covers elements [g*group, (g+1)*group); n_per must be a multiple of
+ *     `group`, so a group never spans two samples.  "Per-row" scaling is
+ *     group == hidden size.
+ *   - codes: the b-bit level index of flat element j occupies bits [j*b, j*b+b) of
+ *     the byte stream, bit k of the stream being bit (k mod 8) of byte k/8.
+ *     aqsgd_codes_bytes() bytes.  scales: one binary32 max-abs per group,
+ *     aqsgd_scales_count() floats; a scale of 0 means "group unchanged".
+ *   - Alignment: act, grad, out, m_buf and codes 16 bytes, scales 4, ids 8.
+ *   - Return value: AQSGD_OK or a negative aqsgd_status.  Everything the host can
+ *     check is checked before any work is enqueued; on error nothing is enqueued.
+ *     NOT checked (undefined results, but no out-of-bounds access as long as ids
+ *     are in range): sample ids outside [0, n_samples), duplicate ids within one
+ *     call (two rows of the call would race on one row of m_buf), non-finite
+ *     inputs.  aqsgd_check_ids() checks the first two on the device.
+ *   - Arithmetic is IEEE binary32 with one rounding per operation and no fused
+ *     multiply-add; stores to float16/bfloat16 round to nearest-even.  Results are
+ *     bit-identical for any launch configuration.
+ */
+#ifndef AQSGD_H
+#define AQSGD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { AQSGD_F32 = 0, AQSGD_F16 = 1, AQSGD_BF16 = 2 } aqsgd_dtype;
+typedef enum { AQSGD_ROUND_NEAREST = 0, AQSGD_ROUND_STOCHASTIC = 1 } aqsgd_round;
+
+typedef enum {
+    AQSGD_OK = 0,
+    AQSGD_ERR_NULL = -1,      /* a required pointer is NULL                         */
+    AQSGD_ERR_BITS = -2,      /* bits not in {2, 3, 4, 8}                           */
+    AQSGD_ERR_GROUP = -3,     /* group <= 0, n_per % group != 0, (group*bits) % 8   */
+    AQSGD_ERR_DTYPE = -4,     /* unknown dtype or rounding mode                     */
+    AQSGD_ERR_SHAPE = -5,     /* negative or overflowing batch / n_per / n_samples  */
+    AQSGD_ERR_ALIGN = -6,     /* a pointer misses its alignment                     */
+    AQSGD_ERR_LAUNCH = -7     /* the HIP runtime refused the launch                 */
+} aqsgd_status;
+
+/* Shape and settings of one call (host memory). */
+typedef struct {
+    int64_t batch;        /* B: samples in this call (0 is allowed: nothing happens) */
+    int64_t n_per;        /* elements per sample (sequence length * hidden size)     */
+    int64_t n_samples;    /* N: rows of m_buf; ignored by the two grad calls         */
+    int32_t bits;         /* b in {2, 3, 4, 8}                                       */
+    int32_t group;        /* G: elements per scale                                   */
+    int32_t dtype;        /* aqsgd_dtype of act / grad / m_buf / out                 */
+    int32_t rounding;     /* aqsgd_round; decode and grad_dequant ignore it          */
+    uint64_t rng_seed;    /* key of the stochastic rounding; use a fresh one per     */
+                          /* message.  Ignored for AQSGD_ROUND_NEAREST               */
+} aqsgd_desc;
+
+/* Bytes of `codes` and number of `scales` for a call of this shape (0 on a bad desc). */
+size_t aqsgd_codes_bytes(const aqsgd_desc* desc);
+size_t aqsgd_scales_count(const aqsgd_desc* desc);
+
+/*
+ * Sender side of the forward message (Algorithm 2, "on network a"; Algorithm 1's
+ * update of m).  For each sample i of the call, with row = sample_ids[i]:
+ *     delta = act[i] - m_buf[row]                     (binary32)
+ *     codes, scales <- Q(delta)                       (Section 4.1)
+ *     m_buf[row] <- dtype(m_buf[row] + Q(delta))      (in place)
+ * m_buf starts as all zeros (Algorithm 1's initialisation), which makes the first
+ * visit of a sample a direct quantisation of its activation.
+ *   act         in   [batch, n_per]
+ *   sample_ids  in   int64[batch], distinct, each in [0, n_samples)
+ *   m_buf       i/o  [n_samples, n_per], the sender's copy
+ *   codes       out  aqsgd_codes_bytes() bytes
+ *   scales      out  aqsgd_scales_count() floats
+ */
+int aqsgd_encode(const aqsgd_desc* desc, const void* act, const int64_t* sample_ids,
+                 void* m_buf, uint8_t* codes, float* scales, void* stream);
+
+/*
+ * Receiver side (Algorithm 2, "on network b"): applies the same update to the
+ * receiver's copy of m and hands m(xi) on as the activation of the next stage.
+ *     m_buf[row] <- dtype(m_buf[row] + Q^-1(codes, scales));  out[i] <- m_buf[row]
+ * After matching encode/decode calls the two copies of m_buf are bit-identical.
+ *   codes, scales  in   as produced by aqsgd_encode with the same desc
+ *   m_buf          i/o  [n_samples, n_per], the receiver's copy
+ *   out            out  [batch, n_per]
+ */
+int aqsgd_decode(const aqsgd_desc* desc, const uint8_t* codes, const float* scales,
+                 const int64_t* sample_ids, void* m_buf, void* out, void* stream);
+
+/*
+ * Backward message (Algorithm 1: "Machine b sends Q(gradient)"): direct
+ * quantisation of the activation-gradient, no buffer.
+ *   grad  in  [batch, n_per];  codes, scales out as above.
+ */
+int aqsgd_grad_quant(const aqsgd_desc* desc, const void* grad, uint8_t* codes,
+                     float* scales, void* stream);
+
+/* Reconstruction of the backward message on the sender: out <- dtype(Q^-1(codes, scales)). */
+int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float* scales,
+                       void* out, void* stream);
+
+/*
+ * Debug helper: checks on the device that sample_ids are distinct and in range.
+ * `flag` is one device int32 the caller has zeroed; the kernel sets bit 0 if an id
+ * is out of range and bit 1 if two ids are equal.  O(batch^2) comparisons.
+ */
+int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
+                    int32_t* flag, void* stream);
+
+/* Human-readable text for a status code (static storage). */
+const char* aqsgd_strerror(int status);
+
+/* Library version, "major.minor.patch". */
+const char* aqsgd_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* AQSGD_H */

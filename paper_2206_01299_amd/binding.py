@@ -1,0 +1,141 @@
+"""Thin ctypes binding over ``libaqsgd.so`` (the C ABI in ``include/aqsgd.h``).
+
+Argument marshalling only: every step of the codec runs in the HIP kernels.
+torch supplies device memory (``tensor.data_ptr()``) and the stream
+(``torch.cuda.current_stream()``); no tensor maths happens here.  There is no
+CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+from pathlib import Path
+
+import torch
+
+_HERE = Path(__file__).resolve().parent
+LIB_PATH = _HERE / "libaqsgd.so"
+
+F32, F16, BF16 = 0, 1, 2
+NEAREST, STOCHASTIC = 0, 1
+
+DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
+DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
+
+EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_check_ids", "aqsgd_strerror",
+           "aqsgd_version")
+
+
+class Desc(ctypes.Structure):
+    """Mirror of ``aqsgd_desc``."""
+    _fields_ = [("batch", ctypes.c_int64), ("n_per", ctypes.c_int64), ("n_samples", ctypes.c_int64),
+                ("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("dtype", ctypes.c_int32),
+                ("rounding", ctypes.c_int32), ("rng_seed", ctypes.c_uint64)]
+
+
+class AqsgdError(RuntimeError):
+    def __init__(self, status: int, text: str):
+        super().__init__(f"aqsgd status {status}: {text}")
+        self.status = status
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library built by ``python -m paper_2206_01299_amd.build``."""
+    global _lib
+    if _lib is None:
+        if not LIB_PATH.exists():
+            raise FileNotFoundError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2206_01299_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(str(LIB_PATH))
+        vp, dp = ctypes.c_void_p, ctypes.POINTER(Desc)
+        L.aqsgd_codes_bytes.restype = ctypes.c_size_t
+        L.aqsgd_codes_bytes.argtypes = [dp]
+        L.aqsgd_scales_count.restype = ctypes.c_size_t
+        L.aqsgd_scales_count.argtypes = [dp]
+        L.aqsgd_encode.restype = ctypes.c_int
+        L.aqsgd_encode.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_decode.restype = ctypes.c_int
+        L.aqsgd_decode.argtypes = [dp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_grad_quant.restype = ctypes.c_int
+        L.aqsgd_grad_quant.argtypes = [dp, vp, vp, vp, vp]
+        L.aqsgd_grad_dequant.restype = ctypes.c_int
+        L.aqsgd_grad_dequant.argtypes = [dp, vp, vp, vp, vp]
+        L.aqsgd_check_ids.restype = ctypes.c_int
+        L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
+        L.aqsgd_strerror.restype = ctypes.c_char_p
+        L.aqsgd_strerror.argtypes = [ctypes.c_int]
+        L.aqsgd_version.restype = ctypes.c_char_p
+        L.aqsgd_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def version() -> str:
+    return lib().aqsgd_version().decode()
+
+
+def strerror(status: int) -> str:
+    return lib().aqsgd_strerror(status).decode()
+
+
+def make_desc(*, batch: int, n_per: int, n_samples: int = 0, bits: int, group: int, dtype,
+              rounding: int = NEAREST, rng_seed: int = 0) -> Desc:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, torch.dtype) else DTYPE_CODE[DTYPE_NAME[dtype]]
+    return Desc(batch, n_per, n_samples, bits, group, code, rounding, rng_seed & 0xFFFFFFFFFFFFFFFF)
+
+
+def codes_bytes(desc: Desc) -> int:
+    return int(lib().aqsgd_codes_bytes(ctypes.byref(desc)))
+
+
+def scales_count(desc: Desc) -> int:
+    return int(lib().aqsgd_scales_count(ctypes.byref(desc)))
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _dev(t: torch.Tensor, what: str) -> ctypes.c_void_p:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{what} must be a contiguous device tensor")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _raise(status: int):
+    if status != 0:
+        raise AqsgdError(status, strerror(status))
+
+
+def encode(desc: Desc, act, sample_ids, m_buf, codes, scales, stream=None) -> None:
+    """``aqsgd_encode``: updates ``m_buf`` in place, fills ``codes`` and ``scales``."""
+    _raise(lib().aqsgd_encode(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
+                              _dev(m_buf, "m_buf"), _dev(codes, "codes"), _dev(scales, "scales"),
+                              _stream(stream)))
+
+
+def decode(desc: Desc, codes, scales, sample_ids, m_buf, out, stream=None) -> None:
+    """``aqsgd_decode``: updates ``m_buf`` in place, fills ``out``."""
+    _raise(lib().aqsgd_decode(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
+                              _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"), _dev(out, "out"),
+                              _stream(stream)))
+
+
+def grad_quant(desc: Desc, grad, codes, scales, stream=None) -> None:
+    _raise(lib().aqsgd_grad_quant(ctypes.byref(desc), _dev(grad, "grad"), _dev(codes, "codes"),
+                                  _dev(scales, "scales"), _stream(stream)))
+
+
+def grad_dequant(desc: Desc, codes, scales, out, stream=None) -> None:
+    _raise(lib().aqsgd_grad_dequant(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
+                                    _dev(out, "out"), _stream(stream)))
+
+
+def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:
+    _raise(lib().aqsgd_check_ids(_dev(sample_ids, "sample_ids"), sample_ids.numel(), n_samples,
+                                 _dev(flag, "flag"), _stream(stream)))

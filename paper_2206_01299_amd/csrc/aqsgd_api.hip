@@ -1,0 +1,283 @@
+// C ABI of the AQ-SGD boundary codec: argument checks and kernel dispatch.
+// See include/aqsgd.h for the contract of every entry point.
+#include <cstdlib>
+#include <limits>
+
+#include "aqsgd_kernels.h"
+
+namespace aqsgd {
+
+// -- dtype fan-out (each dtype's kernels live in their own translation unit) ----
+hipError_t launch_quant_team(int dtype, int bits, int rounding, int shape, LaunchGeom g,
+                             const QuantArgs& a, hipStream_t s) {
+    switch (dtype) {
+    case AQSGD_F32:  return launch_quant_team_dt<AQSGD_F32>(bits, rounding, shape, g, a, s);
+    case AQSGD_F16:  return launch_quant_team_dt<AQSGD_F16>(bits, rounding, shape, g, a, s);
+    case AQSGD_BF16: return launch_quant_team_dt<AQSGD_BF16>(bits, rounding, shape, g, a, s);
+    default:         return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_dequant_flat(int dtype, int bits, int unroll, LaunchGeom g, const DequantArgs& a,
+                               hipStream_t s) {
+    switch (dtype) {
+    case AQSGD_F32:  return launch_dequant_flat_dt<AQSGD_F32>(bits, unroll, g, a, s);
+    case AQSGD_F16:  return launch_dequant_flat_dt<AQSGD_F16>(bits, unroll, g, a, s);
+    case AQSGD_BF16: return launch_dequant_flat_dt<AQSGD_BF16>(bits, unroll, g, a, s);
+    default:         return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, LaunchGeom g, const QuantArgs& a,
+                                 hipStream_t s) {
+    switch (dtype) {
+    case AQSGD_F32:  return launch_quant_anyshape_dt<AQSGD_F32>(bits, rounding, g, a, s);
+    case AQSGD_F16:  return launch_quant_anyshape_dt<AQSGD_F16>(bits, rounding, g, a, s);
+    case AQSGD_BF16: return launch_quant_anyshape_dt<AQSGD_BF16>(bits, rounding, g, a, s);
+    default:         return hipErrorInvalidValue;
+    }
+}
+hipError_t launch_dequant_anyshape(int dtype, int bits, LaunchGeom g, const DequantArgs& a,
+                                   hipStream_t s) {
+    switch (dtype) {
+    case AQSGD_F32:  return launch_dequant_anyshape_dt<AQSGD_F32>(bits, g, a, s);
+    case AQSGD_F16:  return launch_dequant_anyshape_dt<AQSGD_F16>(bits, g, a, s);
+    case AQSGD_BF16: return launch_dequant_anyshape_dt<AQSGD_BF16>(bits, g, a, s);
+    default:         return hipErrorInvalidValue;
+    }
+}
+
+namespace {
+
+// Launch-shape knobs.  They change how the work is cut into workgroups, never a
+// result bit.  Read once from the environment so a sweep needs no rebuild.
+struct Tuning {
+    int64_t max_blocks;      // upper bound on workgroups per launch
+    int dequant_unroll;      // chunks per lane and step in the dequantising kernel (1, 2, 4)
+};
+
+int env_int(const char* name, int fallback) {
+    const char* v = std::getenv(name);
+    if (!v || !*v) return fallback;
+    char* end = nullptr;
+    const long x = std::strtol(v, &end, 10);
+    return (end && *end == '\0' && x > 0 && x < (1L << 30)) ? static_cast<int>(x) : fallback;
+}
+
+const Tuning& tuning() {
+    static const Tuning t = [] {
+        Tuning x;
+        x.max_blocks = env_int("AQSGD_MAX_BLOCKS", 1 << 20);
+        const int u = env_int("AQSGD_DEQUANT_UNROLL", 2);
+        x.dequant_unroll = (u == 1 || u == 2 || u == 4) ? u : 2;
+        return x;
+    }();
+    return t;
+}
+
+constexpr int64_t kMaxGridY = 65535;
+constexpr int kMaxTeamChunks = 4096;     // 1024 lanes x 4 chunks x 8 elements = 32768 elements
+
+bool aligned(const void* p, uintptr_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+
+int check_desc(const aqsgd_desc* d, bool needs_buffer) {
+    if (!d) return AQSGD_ERR_NULL;
+    if (d->dtype != AQSGD_F32 && d->dtype != AQSGD_F16 && d->dtype != AQSGD_BF16) return AQSGD_ERR_DTYPE;
+    if (d->rounding != AQSGD_ROUND_NEAREST && d->rounding != AQSGD_ROUND_STOCHASTIC) return AQSGD_ERR_DTYPE;
+    if (!(d->bits == 2 || d->bits == 3 || d->bits == 4 || d->bits == 8)) return AQSGD_ERR_BITS;
+    if (d->batch < 0 || d->n_per <= 0) return AQSGD_ERR_SHAPE;
+    if (d->group <= 0 || d->n_per % d->group != 0) return AQSGD_ERR_GROUP;
+    if ((static_cast<int64_t>(d->group) * d->bits) % 8 != 0) return AQSGD_ERR_GROUP;
+    const int64_t lim = std::numeric_limits<int64_t>::max() / 16;
+    if (d->batch > std::numeric_limits<int32_t>::max()) return AQSGD_ERR_SHAPE;
+    if (d->n_per > (int64_t{1} << 34)) return AQSGD_ERR_SHAPE;            // chunk index fits 32 bits
+    if (d->batch > 0 && d->n_per > lim / d->batch) return AQSGD_ERR_SHAPE;
+    if (needs_buffer) {
+        if (d->n_samples <= 0 || d->n_per > lim / d->n_samples) return AQSGD_ERR_SHAPE;
+    }
+    return AQSGD_OK;
+}
+
+int team_shape_for(int cpg) {
+    if (cpg <= 8) return kTeam8x1;
+    if (cpg <= 16) return kTeam16x1;
+    if (cpg <= 32) return kTeam32x1;
+    if (cpg <= 64) return kTeam64x1;
+    if (cpg <= 128) return kTeam64x2;
+    if (cpg <= 192) return kTeam64x3;
+    if (cpg <= 256) return kTeam64x4;
+    if (cpg <= 512) return kTeam256x2;
+    if (cpg <= 1024) return kTeam256x4;
+    if (cpg <= 2048) return kTeam1024x2;
+    return kTeam1024x4;
+}
+
+int teams_per_block(int shape) {
+    switch (shape) {
+    case kTeam8x1: return kBlock / 8;
+    case kTeam16x1: return kBlock / 16;
+    case kTeam32x1: return kBlock / 32;
+    case kTeam64x1: case kTeam64x2: case kTeam64x3: case kTeam64x4: return kBlock / 64;
+    default: return 1;
+    }
+}
+
+LaunchGeom geometry(int64_t units_per_sample, int64_t units_per_block, int64_t batch) {
+    LaunchGeom g;
+    const int64_t gy = batch < kMaxGridY ? batch : kMaxGridY;
+    int64_t gx = (units_per_sample + units_per_block - 1) / units_per_block;
+    const int64_t cap = tuning().max_blocks / gy > 0 ? tuning().max_blocks / gy : 1;
+    if (gx > cap) gx = cap;
+    if (gx < 1) gx = 1;
+    g.grid_x = static_cast<unsigned>(gx);
+    g.grid_y = static_cast<unsigned>(gy);
+    return g;
+}
+
+// Quantising side shared by aqsgd_encode and aqsgd_grad_quant.
+int run_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const void* src, const int64_t* ids,
+              void* m_buf, uint8_t* codes, float* scales, hipStream_t stream) {
+    QuantArgs a;
+    a.src = src; a.ids = ids; a.m_buf = m_buf; a.codes = codes; a.scales = scales;
+    a.n_per = n_per; a.gps = n_per / d->group;
+    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
+    a.seed = d->rng_seed;
+    hipError_t err;
+    if (d->group % kChunk == 0 && a.cpg <= kMaxTeamChunks) {
+        const int shape = team_shape_for(a.cpg);
+        err = launch_quant_team(d->dtype, d->bits, d->rounding, shape,
+                                geometry(a.gps, teams_per_block(shape), batch), a, stream);
+    } else {
+        err = launch_quant_anyshape(d->dtype, d->bits, d->rounding, geometry(a.gps, kBlock, batch), a,
+                                    stream);
+    }
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+int run_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t* codes,
+                const float* scales, const int64_t* ids, void* m_buf, void* out, hipStream_t stream) {
+    DequantArgs a;
+    a.codes = codes; a.scales = scales; a.ids = ids; a.m_buf = m_buf; a.out = out;
+    a.n_per = n_per; a.gps = n_per / d->group; a.cps = n_per / kChunk;
+    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
+    hipError_t err;
+    if (d->group % kChunk == 0) {
+        const int unroll = tuning().dequant_unroll;
+        err = launch_dequant_flat(d->dtype, d->bits, unroll,
+                                  geometry(a.cps, static_cast<int64_t>(kBlock) * unroll, batch), a, stream);
+    } else {
+        err = launch_dequant_anyshape(d->dtype, d->bits, geometry(a.gps, kBlock, batch), a, stream);
+    }
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+__global__ void check_ids_kernel(const int64_t* ids, int64_t batch, int64_t n_samples, int32_t* flag) {
+    int bad = 0;
+    for (int64_t i = threadIdx.x + static_cast<int64_t>(blockIdx.x) * blockDim.x; i < batch;
+         i += static_cast<int64_t>(gridDim.x) * blockDim.x) {
+        const int64_t v = ids[i];
+        if (v < 0 || v >= n_samples) bad |= 1;
+        for (int64_t j = 0; j < i; ++j)
+            if (ids[j] == v) bad |= 2;
+    }
+    if (bad) atomicOr(flag, bad);
+}
+
+}  // namespace
+}  // namespace aqsgd
+
+using namespace aqsgd;
+
+extern "C" {
+
+size_t aqsgd_codes_bytes(const aqsgd_desc* d) {
+    if (check_desc(d, false) != AQSGD_OK) return 0;
+    return static_cast<size_t>(d->batch) * static_cast<size_t>(d->n_per) * d->bits / 8;
+}
+
+size_t aqsgd_scales_count(const aqsgd_desc* d) {
+    if (check_desc(d, false) != AQSGD_OK) return 0;
+    return static_cast<size_t>(d->batch) * static_cast<size_t>(d->n_per / d->group);
+}
+
+int aqsgd_encode(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
+                 uint8_t* codes, float* scales, void* stream) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!act || !sample_ids || !m_buf || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(sample_ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return run_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales,
+                     static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_decode(const aqsgd_desc* d, const uint8_t* codes, const float* scales,
+                 const int64_t* sample_ids, void* m_buf, void* out, void* stream) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!codes || !scales || !sample_ids || !m_buf || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(sample_ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return run_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out,
+                       static_cast<hipStream_t>(stream));
+}
+
+// The backward message has no per-sample rows to gather, and n_per is a
+// multiple of the group, so the call tensor is treated as one long sample.
+int aqsgd_grad_quant(const aqsgd_desc* d, const void* grad, uint8_t* codes, float* scales,
+                     void* stream) {
+    const int rc = check_desc(d, false);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!grad || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(grad, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
+    const int64_t n = d->batch * d->n_per;
+    const bool flat = n <= (int64_t{1} << 34);
+    return run_quant(d, flat ? 1 : d->batch, flat ? n : d->n_per, grad, nullptr, nullptr, codes, scales,
+                     static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_grad_dequant(const aqsgd_desc* d, const uint8_t* codes, const float* scales, void* out,
+                       void* stream) {
+    const int rc = check_desc(d, false);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!codes || !scales || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
+    const int64_t n = d->batch * d->n_per;
+    const bool flat = n <= (int64_t{1} << 34);
+    return run_dequant(d, flat ? 1 : d->batch, flat ? n : d->n_per, codes, scales, nullptr, nullptr, out,
+                       static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples, int32_t* flag,
+                    void* stream) {
+    if (batch < 0 || n_samples < 0) return AQSGD_ERR_SHAPE;
+    if (batch == 0) return AQSGD_OK;
+    if (!sample_ids || !flag) return AQSGD_ERR_NULL;
+    if (!aligned(sample_ids, 8) || !aligned(flag, 4)) return AQSGD_ERR_ALIGN;
+    const int64_t blocks = (batch + kBlock - 1) / kBlock;
+    hipLaunchKernelGGL(check_ids_kernel, dim3(static_cast<unsigned>(blocks < 1024 ? blocks : 1024)),
+                       dim3(kBlock), 0, static_cast<hipStream_t>(stream), sample_ids, batch, n_samples, flag);
+    return hipGetLastError() == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+const char* aqsgd_strerror(int status) {
+    switch (status) {
+    case AQSGD_OK:         return "ok";
+    case AQSGD_ERR_NULL:   return "a required pointer is NULL";
+    case AQSGD_ERR_BITS:   return "bits must be 2, 3, 4 or 8";
+    case AQSGD_ERR_GROUP:  return "group must be positive, divide n_per, and hold whole bytes of codes";
+    case AQSGD_ERR_DTYPE:  return "unknown dtype or rounding mode";
+    case AQSGD_ERR_SHAPE:  return "batch / n_per / n_samples negative, zero or too large";
+    case AQSGD_ERR_ALIGN:  return "a pointer misses its required alignment";
+    case AQSGD_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+    default:               return "unknown status";
+    }
+}
+
+const char* aqsgd_version(void) { return "0.1.0"; }
+
+}  // extern "C"

@@ -1,0 +1,299 @@
+// Device-side building blocks of the AQ-SGD boundary codec for gfx950 (CDNA4).
+//
+// Work is organised in "chunks" of 8 consecutive elements: 16 bytes of
+// float16/bfloat16 (one 128-bit access per lane, fully coalesced across a
+// wavefront) or 32 bytes of float32.  Eight b-bit codes are b whole bytes, so a
+// lane's codes never share a byte with a neighbour's.
+//
+// All arithmetic is binary32 with one rounding per operation (the translation
+// unit is compiled with floating-point contraction off); the order of the
+// operations below is part of the wire format: sender, receiver and any other
+// implementation must round in the same places to stay bit-identical.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "aqsgd.h"
+
+namespace aqsgd {
+
+constexpr int kChunk = 8;          // elements per lane-chunk
+constexpr int kWave = 64;          // CDNA wavefront
+
+// ---------------------------------------------------------------------------
+// Storage formats
+// ---------------------------------------------------------------------------
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef float f32x4_t __attribute__((ext_vector_type(4)));
+
+template <int DT> struct ElemBytes { static constexpr int value = 2; };
+template <> struct ElemBytes<AQSGD_F32> { static constexpr int value = 4; };
+
+// One chunk as it sits in memory.
+template <int DT> struct Raw { u32x4_t v; };
+template <> struct Raw<AQSGD_F32> { f32x4_t lo, hi; };
+
+template <int DT>
+__device__ __forceinline__ Raw<DT> load_raw(const void* base, int64_t elem) {
+    Raw<DT> r;
+    if constexpr (DT == AQSGD_F32) {
+        const f32x4_t* p = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(base) + elem);
+        r.lo = __builtin_nontemporal_load(p);
+        r.hi = __builtin_nontemporal_load(p + 1);
+    } else {
+        const u32x4_t* p = reinterpret_cast<const u32x4_t*>(static_cast<const uint16_t*>(base) + elem);
+        r.v = __builtin_nontemporal_load(p);
+    }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ Raw<DT> zero_raw() {
+    Raw<DT> r;
+    if constexpr (DT == AQSGD_F32) { r.lo = f32x4_t{0, 0, 0, 0}; r.hi = r.lo; }
+    else { r.v = u32x4_t{0, 0, 0, 0}; }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void store_raw(void* base, int64_t elem, const Raw<DT>& r) {
+    if constexpr (DT == AQSGD_F32) {
+        f32x4_t* p = reinterpret_cast<f32x4_t*>(static_cast<float*>(base) + elem);
+        __builtin_nontemporal_store(r.lo, p);
+        __builtin_nontemporal_store(r.hi, p + 1);
+    } else {
+        u32x4_t* p = reinterpret_cast<u32x4_t*>(static_cast<uint16_t*>(base) + elem);
+        __builtin_nontemporal_store(r.v, p);
+    }
+}
+
+__device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
+
+// binary32 -> bfloat16, round to nearest even (the top 16 bits of the pattern,
+// rounded on the lower 16; a carry walks into the exponent as it should).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
+    uint32_t u = __float_as_uint(x);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+template <int DT>
+__device__ __forceinline__ void unpack_raw(const Raw<DT>& r, float (&f)[kChunk]) {
+    if constexpr (DT == AQSGD_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { f[e] = r.lo[e]; f[4 + e] = r.hi[e]; }
+    } else if constexpr (DT == AQSGD_F16) {
+        half8_t h = __builtin_bit_cast(half8_t, r.v);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) f[e] = static_cast<float>(h[e]);   // exact
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            f[2 * e] = bf16_bits_to_f32(r.v[e] & 0xffffu);
+            f[2 * e + 1] = __uint_as_float(r.v[e] & 0xffff0000u);
+        }
+    }
+}
+
+template <int DT>
+__device__ __forceinline__ Raw<DT> pack_raw(const float (&f)[kChunk]) {
+    Raw<DT> r;
+    if constexpr (DT == AQSGD_F32) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { r.lo[e] = f[e]; r.hi[e] = f[4 + e]; }
+    } else if constexpr (DT == AQSGD_F16) {
+        half8_t h;
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) h[e] = static_cast<_Float16>(f[e]);  // RNE
+        r.v = __builtin_bit_cast(u32x4_t, h);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            r.v[e] = f32_to_bf16_bits(f[2 * e]) | (f32_to_bf16_bits(f[2 * e + 1]) << 16);
+    }
+    return r;
+}
+
+// Scalar element access for the any-shape fallback kernels.
+template <int DT>
+__device__ __forceinline__ float load_elem(const void* base, int64_t idx) {
+    if constexpr (DT == AQSGD_F32) return static_cast<const float*>(base)[idx];
+    else if constexpr (DT == AQSGD_F16) return static_cast<float>(static_cast<const _Float16*>(base)[idx]);
+    else return bf16_bits_to_f32(static_cast<const uint16_t*>(base)[idx]);
+}
+
+template <int DT>
+__device__ __forceinline__ void store_elem(void* base, int64_t idx, float v) {
+    if constexpr (DT == AQSGD_F32) static_cast<float*>(base)[idx] = v;
+    else if constexpr (DT == AQSGD_F16) static_cast<_Float16*>(base)[idx] = static_cast<_Float16>(v);
+    else static_cast<uint16_t*>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
+}
+
+// ---------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11): counter-based, so element j of a call
+// gets the same draw whatever lane, wave or launch shape computes it.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1,
+                                              uint32_t (&out)[4]) {
+    uint32_t c2 = 0u, c3 = 0u;
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
+        const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
+        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n1 = static_cast<uint32_t>(p1);
+        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n3 = static_cast<uint32_t>(p0);
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ float uniform_from_word(uint32_t w) {
+    return static_cast<float>(w >> 8) * 0x1p-24f;      // 24 bits: exact in binary32
+}
+
+// Rounding offsets of one chunk whose first element has flat index j0 (a
+// multiple of 8): block j0/4 feeds elements 0..3, block j0/4 + 1 elements 4..7.
+__device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint64_t j0, float (&r)[kChunk]) {
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    const uint64_t blk = j0 >> 2;
+    uint32_t w[4];
+    philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), k0, k1, w);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = uniform_from_word(w[e]);
+    const uint64_t blk1 = blk + 1;
+    philox4x32_10(static_cast<uint32_t>(blk1), static_cast<uint32_t>(blk1 >> 32), k0, k1, w);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[4 + e] = uniform_from_word(w[e]);
+}
+
+// ---------------------------------------------------------------------------
+// Max over the TEAM consecutive lanes a lane belongs to (TEAM = 1..64, power of
+// two).  The first four steps are DPP lane permutations inside a 16-lane row;
+// the last two cross rows through ds_bpermute.  Max of non-negative floats is
+// exact and order-free, so any tree gives the same bits.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_max_step(float v) {
+    const int other = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL,
+                                                  0xf, 0xf, false);
+    return __builtin_fmaxf(v, __int_as_float(other));
+}
+
+template <int TEAM>
+__device__ __forceinline__ float team_max(float v) {
+    if constexpr (TEAM >= 2) v = dpp_max_step<0xB1>(v);     // quad_perm [1,0,3,2]
+    if constexpr (TEAM >= 4) v = dpp_max_step<0x4E>(v);     // quad_perm [2,3,0,1]
+    if constexpr (TEAM >= 8) v = dpp_max_step<0x141>(v);    // row_half_mirror
+    if constexpr (TEAM >= 16) v = dpp_max_step<0x140>(v);   // row_mirror
+    if constexpr (TEAM >= 32) v = __builtin_fmaxf(v, __shfl_xor(v, 16, kWave));
+    if constexpr (TEAM >= 64) v = __builtin_fmaxf(v, __shfl_xor(v, 32, kWave));
+    return v;
+}
+
+// ---------------------------------------------------------------------------
+// The quantiser Q on values held in registers.
+// ---------------------------------------------------------------------------
+template <int BITS> struct Levels {
+    static constexpr int top = (1 << BITS) - 1;                         // L
+    static constexpr float half = static_cast<float>((1 << BITS) - 1) / 2.0f;   // L/2, exact
+};
+
+struct GroupScale {
+    float s_tx;     // transmitted scale (0 = nothing to send)
+    float inv;      // (L/2) / s
+    float step;     // s / (L/2)
+};
+
+template <int BITS>
+__device__ __forceinline__ GroupScale make_scale(float max_abs) {
+    GroupScale g;
+    const bool live = !(max_abs < 0x1p-120f);
+    g.s_tx = live ? max_abs : 0.0f;
+    const float denom = live ? max_abs : 1.0f;           // keep the division finite
+    g.inv = Levels<BITS>::half / denom;                  // IEEE-rounded division
+    g.step = denom / Levels<BITS>::half;
+    return g;
+}
+
+// Level index of one value; r = 1/2 (nearest, ties upwards) or U[0,1).
+template <int BITS>
+__device__ __forceinline__ int level_of(float d, float inv, float r) {
+    float t = d * inv;
+    t = t + Levels<BITS>::half;
+    const float y = t + r;
+    const int k = static_cast<int>(__builtin_floorf(y));
+    return min(max(k, 0), Levels<BITS>::top);
+}
+
+template <int BITS>
+__device__ __forceinline__ float value_of(int k, float step) {
+    return (static_cast<float>(k) - Levels<BITS>::half) * step;
+}
+
+// Eight levels -> 8*BITS bits, element e at bits [e*BITS, e*BITS + BITS).
+template <int BITS>
+__device__ __forceinline__ uint64_t pack_levels(const int (&q)[kChunk]) {
+    if constexpr (BITS == 8) {
+        uint32_t lo = 0, hi = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            lo |= static_cast<uint32_t>(q[e]) << (8 * e);
+            hi |= static_cast<uint32_t>(q[4 + e]) << (8 * e);
+        }
+        return (static_cast<uint64_t>(hi) << 32) | lo;
+    } else {
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) w |= static_cast<uint32_t>(q[e]) << (BITS * e);
+        return w;
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ void unpack_levels(uint64_t w, int (&q)[kChunk]) {
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e)
+        q[e] = static_cast<int>((w >> (BITS * e)) & static_cast<uint64_t>(Levels<BITS>::top));
+}
+
+// Codes of one chunk to / from the byte stream; `chunk` is the flat chunk index
+// of the call, so the bytes start at chunk * BITS.
+template <int BITS>
+__device__ __forceinline__ void store_codes(uint8_t* codes, int64_t chunk, uint64_t w) {
+    uint8_t* p = codes + chunk * BITS;
+    if constexpr (BITS == 8) {
+        *reinterpret_cast<uint2*>(p) = make_uint2(static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32));
+    } else if constexpr (BITS == 4) {
+        *reinterpret_cast<uint32_t*>(p) = static_cast<uint32_t>(w);
+    } else if constexpr (BITS == 2) {
+        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(w);
+    } else {
+        p[0] = static_cast<uint8_t>(w);
+        p[1] = static_cast<uint8_t>(w >> 8);
+        p[2] = static_cast<uint8_t>(w >> 16);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ uint64_t load_codes(const uint8_t* codes, int64_t chunk) {
+    const uint8_t* p = codes + chunk * BITS;
+    if constexpr (BITS == 8) {
+        const uint2 v = *reinterpret_cast<const uint2*>(p);
+        return (static_cast<uint64_t>(v.y) << 32) | v.x;
+    } else if constexpr (BITS == 4) {
+        return *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (BITS == 2) {
+        return *reinterpret_cast<const uint16_t*>(p);
+    } else {
+        return static_cast<uint32_t>(p[0]) | (static_cast<uint32_t>(p[1]) << 8) |
+               (static_cast<uint32_t>(p[2]) << 16);
+    }
+}
+
+}  // namespace aqsgd

@@ -1,0 +1,102 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports
+every symbol the header declares, sizes messages as Table 3 implies (b bits per
+element), and turns every host-checkable mistake into an error code before any
+launch."""
+import ctypes
+import re
+from pathlib import Path
+
+import pytest
+
+from paper_2206_01299_amd import binding as B
+
+ROOT = Path(__file__).resolve().parent.parent
+
+
+def test_library_exports_every_declared_symbol():
+    header = (ROOT / "include" / "aqsgd.h").read_text()
+    body = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(aqsgd_[a-z_0-9]+)\s*\(", body))
+    assert declared, "no declarations found in the header"
+    assert declared == set(B.EXPORTS)
+    L = B.lib()
+    for name in declared:
+        assert getattr(L, name) is not None
+    assert re.fullmatch(r"\d+\.\d+\.\d+", B.version())
+
+
+def test_desc_layout_matches_header():
+    assert ctypes.sizeof(B.Desc) == 48
+    assert B.Desc.bits.offset == 24 and B.Desc.rng_seed.offset == 40
+
+
+def test_message_sizes():
+    d = B.make_desc(batch=4, n_per=1024 * 1600, n_samples=8192, bits=4, group=1600, dtype="f16")
+    assert B.codes_bytes(d) == 4 * 1024 * 1600 // 2
+    assert B.scales_count(d) == 4096
+    d = B.make_desc(batch=32, n_per=256 * 1536, n_samples=100_000, bits=3, group=64, dtype="bf16")
+    assert B.codes_bytes(d) == 32 * 256 * 1536 * 3 // 8
+    assert B.scales_count(d) == 32 * 256 * 1536 // 64
+    d = B.make_desc(batch=0, n_per=64, n_samples=1, bits=2, group=64, dtype="f32")
+    assert B.codes_bytes(d) == 0 and B.scales_count(d) == 0
+
+
+BAD = [
+    (dict(bits=5), -2), (dict(bits=0), -2), (dict(bits=16), -2),
+    (dict(group=0), -3), (dict(group=-8), -3), (dict(group=48), -3),     # 48 does not divide 1600
+    (dict(bits=3, group=4, n_per=1600), -3),                              # 12 bits: not whole bytes
+    (dict(bits=2, group=2, n_per=1600), -3),
+    (dict(dtype_code=7), -4), (dict(rounding=2), -4),
+    (dict(batch=-1), -5), (dict(n_per=0), -5), (dict(n_samples=0), -5),
+    (dict(n_samples=2**62), -5), (dict(batch=2**31), -5),
+]
+
+
+@pytest.mark.parametrize("change,status", BAD)
+def test_bad_descriptors_are_rejected_before_any_launch(change, status):
+    kw = dict(batch=4, n_per=1600, n_samples=16, bits=4, group=1600, dtype="f16")
+    dtype_code = change.pop("dtype_code", None) if "dtype_code" in change else None
+    kw.update({k: v for k, v in change.items()})
+    d = B.make_desc(**kw)
+    if dtype_code is not None:
+        d.dtype = dtype_code
+    p = ctypes.c_void_p(4096)          # never dereferenced: the descriptor is refused first
+    L = B.lib()
+    assert L.aqsgd_encode(ctypes.byref(d), p, p, p, p, p, None) == status
+    assert L.aqsgd_decode(ctypes.byref(d), p, p, p, p, p, None) == status
+    if "n_samples" not in change:
+        assert L.aqsgd_grad_quant(ctypes.byref(d), p, p, p, None) == status
+        assert L.aqsgd_grad_dequant(ctypes.byref(d), p, p, p, None) == status
+    assert B.strerror(status) != "unknown status"
+
+
+def test_null_and_misaligned_pointers():
+    d = B.make_desc(batch=4, n_per=1600, n_samples=16, bits=4, group=1600, dtype="f16")
+    L = B.lib()
+    ok = ctypes.c_void_p(4096)
+    odd = ctypes.c_void_p(4096 + 2)
+    assert L.aqsgd_encode(ctypes.byref(d), None, ok, ok, ok, ok, None) == -1
+    assert L.aqsgd_encode(ctypes.byref(d), ok, ok, None, ok, ok, None) == -1
+    assert L.aqsgd_decode(ctypes.byref(d), ok, ok, ok, ok, None, None) == -1
+    assert L.aqsgd_encode(ctypes.byref(d), odd, ok, ok, ok, ok, None) == -6
+    assert L.aqsgd_encode(ctypes.byref(d), ok, ok, odd, ok, ok, None) == -6
+    assert L.aqsgd_decode(ctypes.byref(d), ok, ok, ok, ok, odd, None) == -6
+    assert L.aqsgd_grad_quant(ctypes.byref(d), ok, odd, ok, None) == -6
+    assert L.aqsgd_grad_dequant(ctypes.byref(d), ok, ok, None, None) == -1
+    assert L.aqsgd_encode(None, ok, ok, ok, ok, ok, None) == -1
+    # an empty call succeeds without looking at the pointers
+    d0 = B.make_desc(batch=0, n_per=1600, n_samples=16, bits=4, group=1600, dtype="f16")
+    assert L.aqsgd_encode(ctypes.byref(d0), None, None, None, None, None, None) == 0
+    assert L.aqsgd_decode(ctypes.byref(d0), None, None, None, None, None, None) == 0
+
+
+def test_binding_has_no_cpu_route():
+    """The binding refuses host tensors instead of computing anything itself."""
+    import torch
+    d = B.make_desc(batch=1, n_per=64, n_samples=1, bits=4, group=64, dtype="f32")
+    t = torch.zeros(64)
+    with pytest.raises(ValueError):
+        B.encode(d, t, torch.zeros(1, dtype=torch.int64), t, torch.zeros(32, dtype=torch.uint8),
+                 torch.zeros(1))
+    src = (ROOT / "paper_2206_01299_amd" / "binding.py").read_text()
+    assert "import oracle" not in src and "from oracle" not in src

@@ -1,0 +1,222 @@
+"""GPU parity: the HIP library against the CPU oracle, byte for byte.
+
+Bar (integer codes, binary32 scales, stored m and out): bit-exact, 0 ulp.  Both
+sides decide every level in binary32 with the same operation order, so there is
+no tolerance to state.
+"""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2206_01299_amd import binding as B
+from paper_2206_01299_amd import workloads as W
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; run them with -m gpu on the GPU box")
+    B.lib()                                    # fails loudly if the library is not built
+    import oracle
+    oracle.build()
+    import gpu_harness
+    return gpu_harness
+
+
+@pytest.fixture(autouse=True)
+def _release_device_memory():
+    """The big buffers of one test must not crowd out the next one's."""
+    yield
+    if torch.cuda.is_available():
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+
+
+# ---------------------------------------------------------------------------
+# element-by-element sweeps at sizes the oracle finishes in well under a second:
+# every dtype x bits x rounding, group sizes that hit every kernel shape
+# (sub-wave teams, one wave with 1-4 chunks per lane, multi-wave teams, the
+# any-shape fallback), group counts that leave ragged tails in every tiling.
+# ---------------------------------------------------------------------------
+GROUPS = [8, 24, 64, 128, 200, 256, 520, 1000, 1536, 1600, 2048, 4096, 8200, 16384, 32768]
+ODD_GROUPS = {2: [4, 12, 20], 3: [], 4: [2, 6, 100], 8: [1, 3, 7, 50]}     # not multiples of 8
+HUGE_GROUPS = [40000]                                                       # beyond a workgroup
+
+
+def _case_cfg(dtype, bits, group, rounding, groups_per_sample, batch=3, n_samples=7):
+    return W.BoundaryConfig(
+        name=f"sweep_{dtype}_b{bits}_g{group}_r{rounding}", n_samples=n_samples, batch=batch,
+        seq=groups_per_sample, hidden=group, dtype=dtype, fwd_bits=bits, fwd_group=group,
+        fwd_rounding=rounding, bwd_bits=bits, bwd_group=group, bwd_rounding=rounding,
+        law="normal", drift=0.05, epochs=2, shuffle_ids=True, seed=1000 + bits * 7 + group)
+
+
+def _sweep(H, dtype, bits, group, rounding, gps):
+    cfg = _case_cfg(dtype, bits, group, rounding, gps)
+    quiet = lambda *a, **k: None
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2, log=quiet)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_sweep_group_sizes_nearest(H, dtype, bits):
+    for group in GROUPS:
+        gps = 37 if group <= 2048 else 5
+        print(f"sweep {dtype} b{bits} G{group} nearest", flush=True)
+        _sweep(H, dtype, bits, group, W.NEAREST, gps)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+def test_sweep_group_sizes_stochastic(H, dtype, bits):
+    for group in [8, 64, 128, 1600, 4096, 8200]:
+        gps = 37 if group <= 2048 else 5
+        print(f"sweep {dtype} b{bits} G{group} stochastic", flush=True)
+        _sweep(H, dtype, bits, group, W.STOCHASTIC, gps)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_sweep_any_shape_fallback(H, dtype):
+    for bits, groups in ODD_GROUPS.items():
+        for group in groups:
+            for rounding in (W.NEAREST, W.STOCHASTIC):
+                print(f"fallback {dtype} b{bits} G{group} r{rounding}", flush=True)
+                _sweep(H, dtype, bits, group, rounding, 8 * 131)
+    for group in HUGE_GROUPS:
+        print(f"fallback {dtype} b4 G{group}", flush=True)
+        _sweep(H, dtype, 4, group, W.NEAREST, 3)
+
+
+def test_long_samples_cross_block_strides(H):
+    """Many groups per sample so the grid-stride loops and gridDim.y both turn over."""
+    cfg = _case_cfg("f16", 4, 64, W.NEAREST, groups_per_sample=5000, batch=5, n_samples=11)
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2, log=lambda *a, **k: None)
+    cfg = _case_cfg("bf16", 3, 1600, W.STOCHASTIC, groups_per_sample=1030, batch=2, n_samples=5)
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2, log=lambda *a, **k: None)
+
+
+# ---------------------------------------------------------------------------
+# edge cases
+# ---------------------------------------------------------------------------
+def test_empty_call_touches_nothing(H):
+    d = H.dev()
+    m = torch.ones((4, 256), dtype=torch.float16, device=d)
+    desc = B.make_desc(batch=0, n_per=256, n_samples=4, bits=4, group=64, dtype="f16")
+    e = torch.empty(0, dtype=torch.uint8, device=d)
+    B.encode(desc, torch.empty((0, 256), dtype=torch.float16, device=d),
+             torch.empty(0, dtype=torch.int64, device=d), m, e, torch.empty(0, device=d))
+    torch.cuda.synchronize()
+    assert bool((m == 1).all())
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+def test_unchanged_activation_sends_zero_scale(H, dtype):
+    import oracle
+    d = H.dev()
+    rng = np.random.default_rng(3)
+    m_np = W.to_storage(rng.standard_normal((6, 1024)).astype(np.float32), dtype)
+    ids_np = np.array([5, 0, 3], dtype=np.int64)
+    act_np = np.ascontiguousarray(m_np[ids_np])
+    # one group of the second sample does change, its neighbours do not
+    tweak = W.storage_to_f32(act_np, dtype)
+    tweak[1, 128:192] += 0.25
+    act_np = W.to_storage(tweak, dtype)
+    for bits in (2, 3, 4, 8):
+        m = W.to_torch(m_np.copy(), dtype, d)
+        desc = B.make_desc(batch=3, n_per=1024, n_samples=6, bits=bits, group=64, dtype=dtype)
+        codes = torch.empty(B.codes_bytes(desc), dtype=torch.uint8, device=d)
+        scales = torch.empty(B.scales_count(desc), dtype=torch.float32, device=d)
+        B.encode(desc, W.to_torch(act_np, dtype, d), torch.from_numpy(ids_np).to(d), m, codes, scales)
+        m_host = m_np.copy()
+        wc, ws = oracle.encode(act_np, ids_np, m_host, dtype=dtype, bits=bits, group=64)
+        torch.cuda.synchronize()
+        assert H.same_bytes(codes.cpu().numpy(), wc) and H.same_bytes(scales.cpu().numpy(), ws)
+        assert H.same_bytes(W.from_torch(m, dtype), m_host)
+        assert int((scales == 0).sum()) == 3 * 16 - 1
+
+
+def test_check_ids_flags_duplicates_and_range(H):
+    d = H.dev()
+    for ids, want in [([0, 1, 2, 3], 0), ([0, 9, 2, 3], 1), ([0, 2, 2, 3], 2), ([-1, 5, 5, 1], 3)]:
+        flag = torch.zeros(1, dtype=torch.int32, device=d)
+        B.check_ids(torch.tensor(ids, dtype=torch.int64, device=d), 8, flag)
+        assert int(flag.item()) == want
+
+
+def test_non_default_stream_and_reuse_of_buffers(H):
+    """The call uses the stream it is given; outputs land in caller memory."""
+    cfg = _case_cfg("f16", 4, 1600, W.NEAREST, groups_per_sample=64)
+    s = torch.cuda.Stream()
+    visited = W.parity_ids(cfg, 1)
+    stream = W.ActivationStream(cfg, visited=visited)
+    gpu = H.DeviceBoundary(cfg, stream=s)
+    cpu = H.OracleBoundary(cfg, visited)
+    ids = stream.epoch_ids(0)[0]
+    act = stream.activations(ids, 0)
+    got = gpu.forward(act, ids, 0)
+    want = cpu.forward(act, ids, 0)
+    s.synchronize()
+    H.compare_call("side stream", cfg, got, want)
+
+
+# ---------------------------------------------------------------------------
+# the five workload configurations at their full per-call shapes, with the
+# buffers allocated at full size (row offsets far beyond 2^32 elements) and a
+# few dozen rows visited, first and last row included.
+# ---------------------------------------------------------------------------
+def test_config1_tiny_whole_stream(H):
+    cfg = W.tiny()
+    stats = H.replay_and_compare(cfg, calls_per_epoch=cfg.n_samples // cfg.batch)
+    assert stats["calls"] == 16 * 3
+    s0 = np.mean([s for t, s in stats["mean_scale"] if t == 0])
+    s2 = np.mean([s for t, s in stats["mean_scale"] if t == 2])
+    assert s2 < s0 / 10          # deltas, not activations, are what later epochs send
+
+
+def test_config2_gpt2_4bit_full_shape(H):
+    cfg = W.gpt2_4bit()
+    assert cfg.n_samples * cfg.n_per > 2**32
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2)
+
+
+def test_config3_gpt2_2bit_stochastic_full_shape(H):
+    cfg = W.gpt2_2bit_stochastic()
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=4)
+
+
+def test_config4_deberta_3bit_full_shape(H):
+    cfg = W.deberta_3bit()
+    assert cfg.n_samples * cfg.n_per * 2 > 78e9
+    H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2)
+
+
+def test_config5_stress_eight_boundaries_on_streams(H):
+    """Eight independent boundaries (own buffers, own stream, 2/4/8-bit mix) run
+    concurrently; each must match the oracle, which runs them one after another."""
+    cfgs = [W.stress(b, i) for i, b in enumerate(W.STRESS_BITS)]
+    base = cfgs[0]
+    visited = W.parity_ids(base, 1)
+    src = W.ActivationStream(base, visited=visited)
+    streams = [torch.cuda.Stream() for _ in cfgs]
+    gpus = [H.DeviceBoundary(c, stream=s) for c, s in zip(cfgs, streams)]
+    cpus = [H.OracleBoundary(c, visited) for c in cfgs]
+    for t in range(2):
+        ids = src.epoch_ids(t)[0]
+        act = src.activations(ids, t)                 # the same input feeds every boundary
+        print(f"[stress] epoch {t}: launching 8 boundaries", flush=True)
+        torch.cuda.synchronize()
+        got = [g.forward(act, ids, 0) for g in gpus]  # enqueue all eight before any sync
+        torch.cuda.synchronize()
+        for i, (c, cpu) in enumerate(zip(cfgs, cpus)):
+            want = cpu.forward(act, ids, 0)
+            H.compare_call(f"{c.name} e{t}", c, got[i], want)
+            for which, want_m in (("send", cpu.m_send), ("recv", cpu.m_recv)):
+                assert H.same_bytes(gpus[i].rows(which, cpu.order), want_m)
+            print(f"[stress] epoch {t} boundary {i} b{c.fwd_bits} ok", flush=True)
+        got = None
+    grad = src.gradients(src.epoch_ids(0)[0], 0)
+    gotb = gpus[2].backward(grad, 0)
+    torch.cuda.synchronize()
+    H.compare_call("stress bwd", cfgs[2], gotb, cpus[2].backward(grad, 0))
