@@ -1,0 +1,358 @@
+#!/usr/bin/env python3
+"""Throughput of the AQ-SGD boundary codec on one MI355X.
+
+    python bench.py --gpus 1 --steps K --warmup W
+
+One *step* is one pass of the whole hot path over one micro-batch of the
+GPT2-1.5B-shaped boundary (float16 [4, 1024, 1600], 8192-sample buffers):
+
+    aqsgd_encode   (sender:   gather m rows, delta, per-row scale, 4-bit pack, update m)
+    aqsgd_decode   (receiver: unpack, update its m, emit the activation)
+    aqsgd_grad_quant / aqsgd_grad_dequant   (backward message, 8-bit, direct)
+
+All inputs are resident in HBM before the clock starts.  Buffers rotate: sample ids
+sweep a random permutation of the 8192 rows of the two 26.8 GB buffers and the
+activation / codes / output tensors cycle through pools of > 1 GB each, far beyond
+the 256 MB of last-level cache, so every call reads cold rows from HBM.  The
+buffers are pre-seeded by one full pass and the activations then drift by
+0.05 sigma, so the timed steps encode changes, as in steady-state fine-tuning.
+
+The K timed steps are recorded into HIP graphs (256 steps each) and replayed
+back to back, bracketed by device synchronisation; wall time / K is ms_per_step.
+A second pass over the same K steps launches every kernel through the library's
+timed-launch hook, which stamps a HIP event pair with the kernel's own begin and
+end on its stream; those per-launch durations feed the roofline figure.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+from pathlib import Path
+
+ROOT = Path(__file__).resolve().parent
+for p in (ROOT, ROOT / "tests"):
+    if str(p) not in sys.path:
+        sys.path.insert(0, str(p))
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
+GRAPH_STEPS = 256               # steps recorded per HIP graph
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2048)
+    ap.add_argument("--warmup", type=int, default=128)
+    ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--pool", type=int, default=96, help="micro-batch slots per rotating pool")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-legs", action="store_true")
+    ap.add_argument("--cpu-calls", type=int, default=0, help="oracle sample size (0 = auto)")
+    return ap.parse_args()
+
+
+class Workload:
+    """Device-resident state of the benchmarked boundary."""
+
+    def __init__(self, cfg, pool: int, seed: int = 1234):
+        import torch
+        from paper_2206_01299_amd import binding as B
+        self.torch, self.B, self.cfg = torch, B, cfg
+        d = torch.device("cuda:0")
+        self.dev = d
+        td = B.DTYPE_NAME[cfg.dtype]
+        g = torch.Generator(device=d)
+        g.manual_seed(seed)
+        self.gen = g
+        self.pool = pool
+        Bn, n_per = cfg.batch, cfg.n_per
+
+        self.fdesc = B.make_desc(batch=Bn, n_per=n_per, n_samples=cfg.n_samples, bits=cfg.fwd_bits,
+                                 group=cfg.fwd_group, dtype=cfg.dtype, rounding=cfg.fwd_rounding)
+        self.bdesc = B.make_desc(batch=Bn, n_per=n_per, n_samples=cfg.n_samples, bits=cfg.bwd_bits,
+                                 group=cfg.bwd_group, dtype=cfg.dtype, rounding=cfg.bwd_rounding)
+
+        self.m_send = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
+        self.m_recv = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
+
+        # channel outliers: 1 % of the hidden channels carry 20x the scale
+        chan = torch.ones(cfg.hidden, device=d)
+        k = int(round(cfg.outlier_channel_frac * cfg.hidden))
+        if k:
+            chan[torch.randperm(cfg.hidden, generator=g, device=d)[:k]] = cfg.outlier_scale
+        self.chan = chan
+
+        shape = (pool, Bn, cfg.seq, cfg.hidden)
+        self.act = torch.empty(shape, dtype=td, device=d)
+        self.grad = torch.empty(shape, dtype=td, device=d)
+        for s in range(pool):
+            self.act[s] = (self._draw((Bn, cfg.seq, cfg.hidden)) * chan).to(td)
+            self.grad[s] = (self._draw((Bn, cfg.seq, cfg.hidden)) * (chan * cfg.grad_scale)).to(td)
+        self.out = torch.empty(shape, dtype=td, device=d)
+        self.gout = torch.empty(shape, dtype=td, device=d)
+        self.codes = torch.empty((pool, B.codes_bytes(self.fdesc)), dtype=torch.uint8, device=d)
+        self.scales = torch.empty((pool, B.scales_count(self.fdesc)), dtype=torch.float32, device=d)
+        self.bcodes = torch.empty((pool, B.codes_bytes(self.bdesc)), dtype=torch.uint8, device=d)
+        self.bscales = torch.empty((pool, B.scales_count(self.bdesc)), dtype=torch.float32, device=d)
+
+        perm = torch.randperm(cfg.n_samples, generator=g, device=d)
+        self.ids = perm.view(-1, Bn).contiguous()              # [calls per epoch, B]
+        self.calls = self.ids.shape[0]
+        torch.cuda.synchronize()
+
+    def _draw(self, shape):
+        torch, c = self.torch, self.cfg
+        if c.law == "normal":
+            return torch.randn(shape, device=self.dev, generator=self.gen)
+        raise NotImplementedError(c.law)
+
+    def preseed_and_drift(self):
+        """One full pass (every sample visited once), then the activations drift."""
+        torch, c = self.torch, self.cfg
+        for k in range(self.calls):
+            self.step(k, backward=False)
+        torch.cuda.synchronize()
+        td = self.act.dtype
+        for s in range(self.pool):
+            noise = self._draw(self.act[s].shape) * (self.chan * c.drift)
+            self.act[s] = (self.act[s].float() + noise).to(td)
+        torch.cuda.synchronize()
+
+    # -- the four launches of one step -----------------------------------------
+    def encode(self, k):
+        s = k % self.pool
+        self.B.encode(self.fdesc, self.act[s], self.ids[k % self.calls], self.m_send,
+                      self.codes[s], self.scales[s])
+
+    def decode(self, k):
+        s = k % self.pool
+        self.B.decode(self.fdesc, self.codes[s], self.scales[s], self.ids[k % self.calls],
+                      self.m_recv, self.out[s])
+
+    def grad_quant(self, k):
+        s = k % self.pool
+        self.B.grad_quant(self.bdesc, self.grad[s], self.bcodes[s], self.bscales[s])
+
+    def grad_dequant(self, k):
+        s = k % self.pool
+        self.B.grad_dequant(self.bdesc, self.bcodes[s], self.bscales[s], self.gout[s])
+
+    LEGS = ("encode", "decode", "grad_quant", "grad_dequant")
+
+    def step(self, k, backward=True):
+        self.encode(k)
+        self.decode(k)
+        if backward:
+            self.grad_quant(k)
+            self.grad_dequant(k)
+
+    # -- algorithmic bytes per launch (what the method must move) ----------------
+    def leg_bytes(self):
+        c = self.cfg
+        n, E = c.n, c.elem_bytes
+        fb, bb = c.fwd_bits / 8.0, c.bwd_bits / 8.0
+        fs, bs = 4.0 * n / c.fwd_group, 4.0 * n / c.bwd_group
+        return {
+            "encode": n * (E + E + E + fb) + fs,          # act, m read, m write, codes + scales
+            "decode": n * (fb + E + E + E) + fs,          # codes, m read, m write, out + scales
+            "grad_quant": n * (E + bb) + bs,
+            "grad_dequant": n * (bb + E) + bs,
+        }
+
+
+def timed_steps(wl, first, count, launch):
+    """Run `count` steps starting at step index `first`; returns wall seconds."""
+    torch = wl.torch
+    if launch == "eager":
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for k in range(first, first + count):
+            wl.step(k)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+    graphs = []
+    side = torch.cuda.Stream()
+    k = first
+    while k < first + count:
+        m = min(GRAPH_STEPS, first + count - k)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            for j in range(k, k + m):
+                wl.step(j)
+        graphs.append(g)
+        k += m
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for g in graphs:
+        g.replay()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def kernel_legs(wl, first, count):
+    """Per-launch device durations of every leg over `count` steps (HIP events
+    stamped by the launch itself, on the stream the kernel runs on)."""
+    torch, B = wl.torch, wl.B
+    count = min(count, 1024)
+    pairs = {leg: [] for leg in wl.LEGS}
+    for leg in wl.LEGS:
+        for _ in range(count):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); b.record()                       # creates the HIP events
+            pairs[leg].append((a, b))
+    torch.cuda.synchronize()
+    for i, k in enumerate(range(first, first + count)):
+        for leg in wl.LEGS:
+            a, b = pairs[leg][i]
+            B.profile_next_launch(a, b)
+            getattr(wl, leg)(k)
+    torch.cuda.synchronize()
+    out = {}
+    for leg in wl.LEGS:
+        ms = [a.elapsed_time(b) for a, b in pairs[leg]]
+        ms.sort()
+        out[leg] = {"avg_us": 1e3 * sum(ms) / len(ms), "median_us": 1e3 * ms[len(ms) // 2],
+                    "min_us": 1e3 * ms[0], "launches": len(ms)}
+    return out
+
+
+def cpu_baseline(cfg, calls):
+    """The oracle, as it stands, on this machine's host cores: the same four
+    calls on full-shape micro-batches of the same workload."""
+    import numpy as np
+    import oracle
+    from paper_2206_01299_amd import workloads as W
+    import gpu_harness as H
+    oracle.build()
+    threads = oracle.max_threads()
+    visited = W.parity_ids(cfg, 1)
+    stream = W.ActivationStream(cfg, visited=visited)
+    cpu = H.OracleBoundary(cfg, visited)
+    ids = stream.epoch_ids(0)[0]
+    acts = [stream.activations(ids, t) for t in range(2)]
+    grad = stream.gradients(ids, 0)
+    cpu.forward(acts[0], ids, 0)                                   # seed m: later calls send changes
+    t_once = time.perf_counter()
+    cpu.forward(acts[1], ids, 1)
+    cpu.backward(grad, 1)
+    t_once = time.perf_counter() - t_once
+    if calls <= 0:
+        calls = max(1, min(64, int(15.0 / max(t_once, 1e-3))))
+    t0 = time.perf_counter()
+    for i in range(calls):
+        cpu.forward(acts[i % 2], ids, i)
+        cpu.backward(grad, i)
+    dt = (time.perf_counter() - t0) / calls
+    return {"value": cfg.n * cfg.elem_bytes / dt / 1e9, "unit": "GB/s", "cores": threads,
+            "kind": "oracle", "ms_per_step": dt * 1e3,
+            "sample": f"{calls} full-shape steps (encode+decode+grad_quant+grad_dequant) of "
+                      f"{cfg.name}, 1 micro-batch of {cfg.batch} samples revisited, OpenMP over groups"}
+
+
+def read_traffic():
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
+    counter summary (None if it has not been collected)."""
+    f = ROOT / "profiles" / "hbm_traffic_gpt2_fw4.txt"
+    if not f.exists():
+        return None
+    vals = {}
+    for line in f.read_text().splitlines():
+        if ":" in line and not line.startswith("#"):
+            k, v = line.split(":", 1)
+            try:
+                vals[k.strip()] = float(v.split()[0])
+            except (ValueError, IndexError):
+                pass
+    return vals or None
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the codec of one stage boundary; no collectives). "
+              "Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the codec has no CPU path.", file=sys.stderr)
+        sys.exit(3)
+    from paper_2206_01299_amd import binding as B
+    from paper_2206_01299_amd import workloads as W
+    B.lib()
+
+    cfg = W.gpt2_4bit()
+    K, Wm = args.steps, args.warmup
+    t_setup = time.perf_counter()
+    wl = Workload(cfg, args.pool)
+    wl.preseed_and_drift()
+    t_setup = time.perf_counter() - t_setup
+
+    for k in range(Wm):                                  # untimed warm-up, eager
+        wl.step(k)
+    torch.cuda.synchronize()
+
+    wall = timed_steps(wl, Wm, K, args.launch)
+    ms_per_step = wall / K * 1e3
+    act_bytes = cfg.n * cfg.elem_bytes
+    value = act_bytes / (wall / K) / 1e9
+
+    legs = None if args.no_kernel_legs else kernel_legs(wl, Wm, K)
+    lb = wl.leg_bytes()
+    roofline = None
+    extra = {}
+    if legs:
+        dominant = max(wl.LEGS, key=lambda l: legs[l]["avg_us"])
+        a_gbps = lb[dominant] / (legs[dominant]["avg_us"] * 1e-6) / 1e9
+        traffic = read_traffic()
+        roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(a_gbps, 1),
+                    "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
+                    "algorithmic_bytes_per_launch": lb[dominant],
+                    "avg_launch_us": round(legs[dominant]["avg_us"], 3),
+                    "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch")}
+        pair_us = legs["encode"]["avg_us"] + legs["decode"]["avg_us"]
+        pair_bytes = lb["encode"] + lb["decode"]
+        extra["fwd_pair"] = {"us": round(pair_us, 3),
+                             "act_GBps": round(act_bytes / pair_us / 1e3, 1),
+                             "hbm_GBps": round(pair_bytes / pair_us / 1e3, 1),
+                             "frac_of_hbm_peak": round(pair_bytes / pair_us / 1e3 / HBM_PEAK_GBPS, 4)}
+        extra["kernels"] = {l: {"avg_us": round(legs[l]["avg_us"], 3),
+                                "median_us": round(legs[l]["median_us"], 3),
+                                "hbm_GBps": round(lb[l] / legs[l]["avg_us"] / 1e3, 1)} for l in wl.LEGS}
+    step_bytes = sum(lb.values())
+    extra["step_hbm_GBps"] = round(step_bytes / (wall / K) / 1e9, 1)
+    extra["step_frac_of_hbm_peak"] = round(step_bytes / (wall / K) / 1e9 / HBM_PEAK_GBPS, 4)
+
+    base = None
+    if not args.no_cpu_baseline:
+        base = cpu_baseline(cfg, args.cpu_calls)
+        base["value"] = round(base["value"], 4)
+        base["ms_per_step"] = round(base["ms_per_step"], 2)
+
+    line = {
+        "metric": "encode+decode GB/s of activations (and % HBM peak), 4-bit GPT2-1.5B boundary",
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "GPT2-1.5B-shaped stage boundary: float16 activations [4,1024,1600], "
+                               "8192-sample float16 m_buf x2 (sender, receiver), forward 4-bit "
+                               "per-row delta codec, backward 8-bit direct; one step = encode + "
+                               "decode + grad_quant + grad_dequant; value = activation bytes of one "
+                               "micro-batch / step time",
+                   "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
+                   "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
+                   "group": cfg.fwd_group, "pool_slots": args.pool, "launch": args.launch,
+                   "cold_buffers": True, "device": torch.cuda.get_device_name(0),
+                   "setup_s": round(t_setup, 1)},
+        "roofline": roofline, "cpu_baseline": base,
+    }
+    line.update(extra)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

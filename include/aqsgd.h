@@ -135,6 +135,16 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
 int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
                     int32_t* flag, void* stream);
 
+/*
+ * Measurement helper: the next codec launch made by the calling host thread
+ * stamps `start_event` and `stop_event` (hipEvent_t created with timing enabled,
+ * passed as void*; either may be NULL) with the kernel's own begin and end, so
+ * hipEventElapsedTime(start, stop) is that launch's duration on the device.  The
+ * request applies to one launch and is then cleared.  Such a launch cannot be
+ * recorded into a HIP graph.
+ */
+int aqsgd_profile_next_launch(void* start_event, void* stop_event);
+
 /* Human-readable text for a status code (static storage). */
 const char* aqsgd_strerror(int status);
 

@@ -22,8 +22,8 @@ DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
-           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_check_ids", "aqsgd_strerror",
-           "aqsgd_version")
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_check_ids",
+           "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
 class Desc(ctypes.Structure):
@@ -66,6 +66,8 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_grad_dequant.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_check_ids.restype = ctypes.c_int
         L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
+        L.aqsgd_profile_next_launch.restype = ctypes.c_int
+        L.aqsgd_profile_next_launch.argtypes = [vp, vp]
         L.aqsgd_strerror.restype = ctypes.c_char_p
         L.aqsgd_strerror.argtypes = [ctypes.c_int]
         L.aqsgd_version.restype = ctypes.c_char_p
@@ -139,3 +141,11 @@ def grad_dequant(desc: Desc, codes, scales, out, stream=None) -> None:
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:
     _raise(lib().aqsgd_check_ids(_dev(sample_ids, "sample_ids"), sample_ids.numel(), n_samples,
                                  _dev(flag, "flag"), _stream(stream)))
+
+
+def profile_next_launch(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> None:
+    """Have the next codec launch of this thread stamp two timing events with the
+    kernel's own begin and end.  The events must already exist on the device
+    (a torch event is created by its first ``record()``)."""
+    _raise(lib().aqsgd_profile_next_launch(ctypes.c_void_p(start.cuda_event),
+                                           ctypes.c_void_p(stop.cuda_event)))

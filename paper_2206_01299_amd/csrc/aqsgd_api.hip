@@ -7,6 +7,8 @@
 
 namespace aqsgd {
 
+thread_local ProfileRequest g_profile_request = {nullptr, nullptr};
+
 // -- dtype fan-out (each dtype's kernels live in their own translation unit) ----
 hipError_t launch_quant_team(int dtype, int bits, int rounding, int shape, LaunchGeom g,
                              const QuantArgs& a, hipStream_t s) {
@@ -262,6 +264,12 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
     hipLaunchKernelGGL(check_ids_kernel, dim3(static_cast<unsigned>(blocks < 1024 ? blocks : 1024)),
                        dim3(kBlock), 0, static_cast<hipStream_t>(stream), sample_ids, batch, n_samples, flag);
     return hipGetLastError() == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+int aqsgd_profile_next_launch(void* start_event, void* stop_event) {
+    g_profile_request.start = static_cast<hipEvent_t>(start_event);
+    g_profile_request.stop = static_cast<hipEvent_t>(stop_event);
+    return AQSGD_OK;
 }
 
 const char* aqsgd_strerror(int status) {

@@ -49,6 +49,31 @@ __device__ __forceinline__ Raw<DT> load_raw(const void* base, int64_t elem) {
     return r;
 }
 
+// Same, at a byte address.
+template <int DT>
+__device__ __forceinline__ Raw<DT> load_raw_at(const char* p) {
+    Raw<DT> r;
+    if constexpr (DT == AQSGD_F32) {
+        const f32x4_t* q = reinterpret_cast<const f32x4_t*>(p);
+        r.lo = __builtin_nontemporal_load(q);
+        r.hi = __builtin_nontemporal_load(q + 1);
+    } else {
+        r.v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(p));
+    }
+    return r;
+}
+
+template <int DT>
+__device__ __forceinline__ void store_raw_at(char* p, const Raw<DT>& r) {
+    if constexpr (DT == AQSGD_F32) {
+        f32x4_t* q = reinterpret_cast<f32x4_t*>(p);
+        __builtin_nontemporal_store(r.lo, q);
+        __builtin_nontemporal_store(r.hi, q + 1);
+    } else {
+        __builtin_nontemporal_store(r.v, reinterpret_cast<u32x4_t*>(p));
+    }
+}
+
 template <int DT>
 __device__ __forceinline__ Raw<DT> zero_raw() {
     Raw<DT> r;
@@ -114,6 +139,68 @@ __device__ __forceinline__ Raw<DT> pack_raw(const float (&f)[kChunk]) {
             r.v[e] = f32_to_bf16_bits(f[2 * e]) | (f32_to_bf16_bits(f[2 * e + 1]) << 16);
     }
     return r;
+}
+
+// float16 operands enter binary32 arithmetic through v_fma_mix_f32, which widens
+// a half (low or high 16 bits of a register) on the fly: x * 1.0 + y is exact in
+// the product and rounds the sum once, so it is the same binary32 add/subtract,
+// without a separate conversion instruction per operand.
+__device__ __forceinline__ float f16lo_minus_f16lo(uint32_t a, uint32_t m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel_hi:[1,0,1]" : "=v"(d) : "v"(a), "v"(m));
+    return d;
+}
+__device__ __forceinline__ float f16hi_minus_f16hi(uint32_t a, uint32_t m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,1] op_sel_hi:[1,0,1]" : "=v"(d) : "v"(a), "v"(m));
+    return d;
+}
+__device__ __forceinline__ float f32_plus_f16lo(float x, uint32_t m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel_hi:[0,0,1]" : "=v"(d) : "v"(x), "v"(m));
+    return d;
+}
+__device__ __forceinline__ float f32_plus_f16hi(float x, uint32_t m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[0,0,1] op_sel_hi:[0,0,1]" : "=v"(d) : "v"(x), "v"(m));
+    return d;
+}
+
+// d[e] = binary32(a[e]) - binary32(m[e]) for one chunk.
+template <int DT>
+__device__ __forceinline__ void delta_chunk(const Raw<DT>& a, const Raw<DT>& m, float (&d)[kChunk]) {
+    if constexpr (DT == AQSGD_F16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            d[2 * e] = f16lo_minus_f16lo(a.v[e], m.v[e]);
+            d[2 * e + 1] = f16hi_minus_f16hi(a.v[e], m.v[e]);
+        }
+    } else {
+        float av[kChunk], mv[kChunk];
+        unpack_raw<DT>(a, av);
+        unpack_raw<DT>(m, mv);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) d[e] = av[e] - mv[e];
+    }
+}
+
+// storage(binary32(m[e]) + x[e]) for one chunk.
+template <int DT>
+__device__ __forceinline__ Raw<DT> updated_chunk(const Raw<DT>& m, const float (&x)[kChunk]) {
+    float s[kChunk];
+    if constexpr (DT == AQSGD_F16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            s[2 * e] = f32_plus_f16lo(x[2 * e], m.v[e]);
+            s[2 * e + 1] = f32_plus_f16hi(x[2 * e + 1], m.v[e]);
+        }
+    } else {
+        float mv[kChunk];
+        unpack_raw<DT>(m, mv);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) s[e] = mv[e] + x[e];
+    }
+    return pack_raw<DT>(s);
 }
 
 // Scalar element access for the any-shape fallback kernels.
@@ -204,36 +291,60 @@ template <int BITS> struct Levels {
     static constexpr float half = static_cast<float>((1 << BITS) - 1) / 2.0f;   // L/2, exact
 };
 
+// Per-group constants.  A group whose max-abs is below 2^-120 sends scale 0,
+// level 0 everywhere and reconstructs +0: with inv = offset = step = 0 the
+// element formulas below give exactly that (0*d + 0 + r < 1 -> level 0;
+// (0 - 0) * 0 = +0), so the per-element code carries no special case.
 struct GroupScale {
     float s_tx;     // transmitted scale (0 = nothing to send)
     float inv;      // (L/2) / s
-    float step;     // s / (L/2)
+    float offset;   // L/2: position of value 0 on the level axis
+    float step;     // s / (L/2): level spacing
 };
 
 template <int BITS>
 __device__ __forceinline__ GroupScale make_scale(float max_abs) {
     GroupScale g;
     const bool live = !(max_abs < 0x1p-120f);
+    const float denom = live ? max_abs : 1.0f;           // keep the divisions finite
+    const float inv = Levels<BITS>::half / denom;        // IEEE-rounded divisions
+    const float step = denom / Levels<BITS>::half;
     g.s_tx = live ? max_abs : 0.0f;
-    const float denom = live ? max_abs : 1.0f;           // keep the division finite
-    g.inv = Levels<BITS>::half / denom;                  // IEEE-rounded division
-    g.step = denom / Levels<BITS>::half;
+    g.inv = live ? inv : 0.0f;
+    g.offset = live ? Levels<BITS>::half : 0.0f;
+    g.step = live ? step : 0.0f;
+    return g;
+}
+
+// Receiver's view: the same constants from the transmitted scale.
+template <int BITS>
+__device__ __forceinline__ GroupScale scale_from_wire(float s_tx) {
+    GroupScale g;
+    const bool live = s_tx != 0.0f;
+    g.s_tx = s_tx;
+    g.inv = 0.0f;
+    g.offset = live ? Levels<BITS>::half : 0.0f;
+    g.step = live ? s_tx / Levels<BITS>::half : 0.0f;
     return g;
 }
 
 // Level index of one value; r = 1/2 (nearest, ties upwards) or U[0,1).
-template <int BITS>
-__device__ __forceinline__ int level_of(float d, float inv, float r) {
-    float t = d * inv;
-    t = t + Levels<BITS>::half;
+// y = ((d * inv) + L/2) + r is never below -2^-20, so converting towards zero is
+// floor() followed by the clamp at 0.  With r = 1/2, |d| <= s bounds y below
+// L + 1, so no upper clamp is needed; a stochastic r can reach L + 1.
+template <int BITS, int ROUND>
+__device__ __forceinline__ int level_of(float d, const GroupScale& g, float r) {
+    float t = d * g.inv;
+    t = t + g.offset;
     const float y = t + r;
-    const int k = static_cast<int>(__builtin_floorf(y));
-    return min(max(k, 0), Levels<BITS>::top);
+    const int k = static_cast<int>(y);
+    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) return min(k, Levels<BITS>::top);
+    else return k;
 }
 
 template <int BITS>
-__device__ __forceinline__ float value_of(int k, float step) {
-    return (static_cast<float>(k) - Levels<BITS>::half) * step;
+__device__ __forceinline__ float value_of(int k, const GroupScale& g) {
+    return (static_cast<float>(k) - g.offset) * g.step;
 }
 
 // Eight levels -> 8*BITS bits, element e at bits [e*BITS, e*BITS + BITS).
@@ -262,11 +373,10 @@ __device__ __forceinline__ void unpack_levels(uint64_t w, int (&q)[kChunk]) {
         q[e] = static_cast<int>((w >> (BITS * e)) & static_cast<uint64_t>(Levels<BITS>::top));
 }
 
-// Codes of one chunk to / from the byte stream; `chunk` is the flat chunk index
-// of the call, so the bytes start at chunk * BITS.
+// Codes of one chunk to / from the byte stream; chunk c of the call starts at
+// byte c * BITS.
 template <int BITS>
-__device__ __forceinline__ void store_codes(uint8_t* codes, int64_t chunk, uint64_t w) {
-    uint8_t* p = codes + chunk * BITS;
+__device__ __forceinline__ void store_codes_at(uint8_t* p, uint64_t w) {
     if constexpr (BITS == 8) {
         *reinterpret_cast<uint2*>(p) = make_uint2(static_cast<uint32_t>(w), static_cast<uint32_t>(w >> 32));
     } else if constexpr (BITS == 4) {
@@ -281,8 +391,7 @@ __device__ __forceinline__ void store_codes(uint8_t* codes, int64_t chunk, uint6
 }
 
 template <int BITS>
-__device__ __forceinline__ uint64_t load_codes(const uint8_t* codes, int64_t chunk) {
-    const uint8_t* p = codes + chunk * BITS;
+__device__ __forceinline__ uint64_t load_codes_at(const uint8_t* p) {
     if constexpr (BITS == 8) {
         const uint2 v = *reinterpret_cast<const uint2*>(p);
         return (static_cast<uint64_t>(v.y) << 32) | v.x;

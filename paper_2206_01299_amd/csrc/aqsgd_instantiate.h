@@ -10,9 +10,8 @@ namespace aqsgd {
 template <int DT, int BITS, int ROUND, int TEAM, int CPL>
 static hipError_t launch_qt(LaunchGeom g, const QuantArgs& a, hipStream_t stream) {
     constexpr int threads = TEAM > kBlock ? TEAM : kBlock;
-    hipLaunchKernelGGL((quant_team_kernel<DT, BITS, ROUND, TEAM, CPL>), dim3(g.grid_x, g.grid_y),
-                       dim3(threads), 0, stream, a);
-    return hipGetLastError();
+    return launch_kernel(quant_team_kernel<DT, BITS, ROUND, TEAM, CPL>, dim3(g.grid_x, g.grid_y),
+                         dim3(threads), stream, a);
 }
 
 template <int DT, int BITS, int ROUND>
@@ -57,12 +56,11 @@ template <int DT, int BITS>
 static hipError_t launch_df_unroll(int unroll, LaunchGeom g, const DequantArgs& a, hipStream_t stream) {
     const dim3 grid(g.grid_x, g.grid_y), block(kBlock);
     switch (unroll) {
-    case 1: hipLaunchKernelGGL((dequant_flat_kernel<DT, BITS, 1>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((dequant_flat_kernel<DT, BITS, 2>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((dequant_flat_kernel<DT, BITS, 4>), grid, block, 0, stream, a); break;
+    case 1: return launch_kernel(dequant_flat_kernel<DT, BITS, 1>, grid, block, stream, a);
+    case 2: return launch_kernel(dequant_flat_kernel<DT, BITS, 2>, grid, block, stream, a);
+    case 4: return launch_kernel(dequant_flat_kernel<DT, BITS, 4>, grid, block, stream, a);
     default: return hipErrorInvalidValue;
     }
-    return hipGetLastError();
 }
 
 template <int DT>
@@ -80,16 +78,14 @@ hipError_t launch_dequant_flat_dt(int bits, int unroll, LaunchGeom g, const Dequ
 template <int DT>
 hipError_t launch_quant_anyshape_dt(int bits, int rounding, LaunchGeom g, const QuantArgs& a,
                                     hipStream_t stream) {
-    hipLaunchKernelGGL((quant_anyshape_kernel<DT>), dim3(g.grid_x, g.grid_y), dim3(kBlock), 0, stream,
-                       a, bits, rounding);
-    return hipGetLastError();
+    return launch_kernel(quant_anyshape_kernel<DT>, dim3(g.grid_x, g.grid_y), dim3(kBlock), stream, a,
+                         bits, rounding);
 }
 
 template <int DT>
 hipError_t launch_dequant_anyshape_dt(int bits, LaunchGeom g, const DequantArgs& a, hipStream_t stream) {
-    hipLaunchKernelGGL((dequant_anyshape_kernel<DT>), dim3(g.grid_x, g.grid_y), dim3(kBlock), 0, stream,
-                       a, bits);
-    return hipGetLastError();
+    return launch_kernel(dequant_anyshape_kernel<DT>, dim3(g.grid_x, g.grid_y), dim3(kBlock), stream, a,
+                         bits);
 }
 
 #define AQSGD_INSTANTIATE_DTYPE(DT)                                                               \

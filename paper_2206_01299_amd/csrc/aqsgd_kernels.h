@@ -17,9 +17,19 @@
 // inside a sample, so no index needs a 64-bit division on the device.
 #pragma once
 
+#include <hip/hip_ext.h>
+
+#include <tuple>
+#include <utility>
+
 #include "aqsgd_device.h"
 
 namespace aqsgd {
+
+template <typename Tuple, size_t... I>
+void fill_arg_pointers(Tuple& t, void** argv, std::index_sequence<I...>) {
+    ((argv[I] = static_cast<void*>(&std::get<I>(t))), ...);
+}
 
 struct QuantArgs {
     const void* src;           // act or grad  [batch, n_per]
@@ -52,157 +62,201 @@ struct DequantArgs {
 constexpr int kBlock = 256;
 
 // ---------------------------------------------------------------------------
-// encode / grad_quant, team kernel
+// encode / grad_quant, team kernel.
+//
+// One step of a workgroup covers kTeamsPerBlock consecutive groups, one per
+// team.  Lanes past the end of a group do not branch around their loads: they
+// re-read the group's last chunk, whose values are already in the maximum, hold
+// a copy of its results (loaded by the same instruction as the original) and
+// store the same bytes to the same place.  Only a team past the last group of
+// the sample (ragged last step) is switched off, as a whole.
 // ---------------------------------------------------------------------------
-template <int DT, int BITS, int ROUND, int TEAM, int CPL>
-__global__ __launch_bounds__((TEAM > kBlock ? TEAM : kBlock))
-void quant_team_kernel(const QuantArgs a) {
+template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
+__device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char* src_s, char* m_s,
+                                                 uint8_t* codes_s, float* scales_s, int64_t src0,
+                                                 int64_t g, const uint32_t (&cc)[CPL],
+                                                 int lane_in_team, float* wave_max) {
+    constexpr bool kMultiWave = TEAM > kWave;
+    constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
+    constexpr int kEB = ElemBytes<DT>::value;
+    constexpr int kChunkBytes = kChunk * kEB;
+
+    // ---- issue every load of the group ------------------------------------------
+    const int64_t goff = g * a.group;                    // element offset within the sample
+    Raw<DT> ra[CPL], rm[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        ra[k] = load_raw_at<DT>(src_s + goff * kEB + cc[k] * kChunkBytes);
+        if constexpr (HAS_BUF) rm[k] = load_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes);
+        else rm[k] = zero_raw<DT>();
+    }
+
+    // ---- delta and the group's max-abs --------------------------------------------
+    float d[CPL][kChunk];
+    float mx = 0.0f;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        delta_chunk<DT>(ra[k], rm[k], d[k]);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) mx = __builtin_fmaxf(mx, __builtin_fabsf(d[k][e]));
+    }
+    mx = team_max<(TEAM < kWave ? TEAM : kWave)>(mx);
+    if constexpr (kMultiWave) {                          // the whole workgroup is in here
+        __syncthreads();                                 // earlier readers of wave_max are done
+        if (threadIdx.x % kWave == 0) wave_max[threadIdx.x / kWave] = mx;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kThreads / kWave; ++w) mx = __builtin_fmaxf(mx, wave_max[w]);
+    }
+    const GroupScale sc = make_scale<BITS>(mx);
+
+    // ---- quantise, pack, update m ---------------------------------------------------
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        float r[kChunk];
+        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
+            chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
+        }
+        int q[kChunk];
+        float dh[kChunk];
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) {
+            q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[e]);
+            dh[e] = value_of<BITS>(q[e], sc);
+        }
+        store_codes_at<BITS>(codes_s + goff / kChunk * BITS + cc[k] * BITS, pack_levels<BITS>(q));
+        if constexpr (HAS_BUF)
+            store_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes, updated_chunk<DT>(rm[k], dh));
+    }
+    if (lane_in_team == 0) scales_s[g] = sc.s_tx;
+}
+
+template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
+__device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
     constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
     constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
-    static_assert(!kMultiWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
+    constexpr int kEB = ElemBytes<DT>::value;
 
     const int lane_in_team = threadIdx.x % TEAM;
-    const int team = threadIdx.x / TEAM;
-    const bool has_buf = a.m_buf != nullptr;
-    [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
+    // A team of at least one wavefront has a wave-uniform index: say so, and the
+    // group's base addresses stay in scalar registers.
+    const int team = kMultiWave ? 0
+                     : (TEAM == kWave ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave)
+                                      : static_cast<int>(threadIdx.x / TEAM));
+
+    uint32_t cc[CPL];           // this lane's chunks within a group, clamped to the last one
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+        cc[k] = static_cast<uint32_t>(min(k * TEAM + lane_in_team, a.cpg - 1));
 
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;      // flat offset of sample i
-        const int64_t m0 = row * a.n_per;
+        const char* src_s = static_cast<const char*>(a.src) + src0 * kEB;
+        char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
+        uint8_t* codes_s = a.codes + src0 / kChunk * BITS;
+        float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
         for (int64_t gbase = static_cast<int64_t>(blockIdx.x) * kTeamsPerBlock; gbase < a.gps;
              gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
-            const int64_t gs = gbase + team;                 // group within the sample
-            const bool group_ok = gs < a.gps;
-            const int64_t goff = gs * a.group;               // element offset within the sample
-
-            // ---- issue every load of the group -------------------------------
-            Raw<DT> ra[CPL], rm[CPL];
-            bool ok[CPL];
-#pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                const int c = k * TEAM + lane_in_team;
-                ok[k] = group_ok && c < a.cpg;
-                ra[k] = zero_raw<DT>();
-                rm[k] = zero_raw<DT>();
-                if (ok[k]) {
-                    ra[k] = load_raw<DT>(a.src, src0 + goff + static_cast<int64_t>(c) * kChunk);
-                    if (has_buf) rm[k] = load_raw<DT>(a.m_buf, m0 + goff + static_cast<int64_t>(c) * kChunk);
-                }
-            }
-
-            // ---- delta and the group's max-abs -----------------------------------
-            float d[CPL][kChunk], m_old[CPL][kChunk];
-            float mx = 0.0f;
-#pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                float av[kChunk];
-                unpack_raw<DT>(ra[k], av);
-                unpack_raw<DT>(rm[k], m_old[k]);
-#pragma unroll
-                for (int e = 0; e < kChunk; ++e) {
-                    d[k][e] = av[e] - m_old[k][e];
-                    mx = __builtin_fmaxf(mx, __builtin_fabsf(d[k][e]));
-                }
-            }
-            mx = team_max<(TEAM < kWave ? TEAM : kWave)>(mx);
-            if constexpr (kMultiWave) {
-                __syncthreads();                                 // previous round's readers are done
-                if (threadIdx.x % kWave == 0) wave_max[threadIdx.x / kWave] = mx;
-                __syncthreads();
-#pragma unroll
-                for (int w = 0; w < kThreads / kWave; ++w) mx = __builtin_fmaxf(mx, wave_max[w]);
-            }
-            const GroupScale sc = make_scale<BITS>(mx);
-            const bool live = sc.s_tx != 0.0f;
-
-            // ---- quantise, pack, update m ----------------------------------------
-#pragma unroll
-            for (int k = 0; k < CPL; ++k) {
-                const int c = k * TEAM + lane_in_team;
-                const int64_t e0 = goff + static_cast<int64_t>(c) * kChunk;   // within the sample
-                float r[kChunk];
-                if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
-                    chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + e0), r);
-                } else {
-#pragma unroll
-                    for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
-                }
-                int q[kChunk];
-                float m_new[kChunk];
-#pragma unroll
-                for (int e = 0; e < kChunk; ++e) {
-                    const int kq = level_of<BITS>(d[k][e], sc.inv, r[e]);
-                    q[e] = live ? kq : 0;
-                    const float dh = live ? value_of<BITS>(kq, sc.step) : 0.0f;
-                    m_new[e] = m_old[k][e] + dh;
-                }
-                if (ok[k]) {
-                    store_codes<BITS>(a.codes, (src0 + e0) / kChunk, pack_levels<BITS>(q));
-                    if (has_buf) store_raw<DT>(a.m_buf, m0 + e0, pack_raw<DT>(m_new));
-                }
-            }
-            if (group_ok && lane_in_team == 0)
-                a.scales[static_cast<int64_t>(i) * a.gps + gs] = sc.s_tx;
+            const int64_t g = gbase + team;              // uniform over the team
+            if (g < a.gps)
+                quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF>(a, src_s, m_s, codes_s, scales_s,
+                                                                      src0, g, cc, lane_in_team, wave_max);
         }
     }
 }
 
+template <int DT, int BITS, int ROUND, int TEAM, int CPL>
+__global__ __launch_bounds__((TEAM > kBlock ? TEAM : kBlock))
+void quant_team_kernel(const QuantArgs a) {
+    constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
+    static_assert(TEAM <= kWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
+    [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
+    if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, wave_max);
+    else quant_team_body<DT, BITS, ROUND, TEAM, CPL, false>(a, wave_max);
+}
+
 // ---------------------------------------------------------------------------
-// decode / grad_dequant, flat chunk kernel: UNROLL chunks per lane and step.
+// decode / grad_dequant, flat chunk kernel: UNROLL chunks per lane and step, all
+// loads first.  The group of a chunk comes from one exact division per
+// workgroup step plus a small per-lane correction.
 // ---------------------------------------------------------------------------
-template <int DT, int BITS, int UNROLL>
-__global__ __launch_bounds__(kBlock)
-void dequant_flat_kernel(const DequantArgs a) {
-    const bool has_buf = a.m_buf != nullptr;
+template <int DT, int BITS, int UNROLL, bool HAS_BUF>
+__device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
+    constexpr int kEB = ElemBytes<DT>::value;
+    constexpr int kChunkBytes = kChunk * kEB;
+    constexpr uint32_t kStep = kBlock * UNROLL;
     const uint32_t cpg = static_cast<uint32_t>(a.cpg);
+    const float rcp_cpg = 1.0f / static_cast<float>(cpg);
+    const uint32_t cps = static_cast<uint32_t>(a.cps);
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
-        const int64_t m0 = row * a.n_per;
-        const float* scales_i = a.scales + static_cast<int64_t>(i) * a.gps;
+        char* out_s = static_cast<char*>(a.out) + out0 * kEB;
+        char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
+        const uint8_t* codes_s = a.codes + out0 / kChunk * BITS;
+        const float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
-        for (int64_t cbase = static_cast<int64_t>(blockIdx.x) * (kBlock * UNROLL); cbase < a.cps;
-             cbase += static_cast<int64_t>(gridDim.x) * (kBlock * UNROLL)) {
+        for (uint32_t cbase = blockIdx.x * kStep; cbase < cps; cbase += gridDim.x * kStep) {
+            // group and position of the step's first chunk (uniform), then per lane
+            const uint32_t g0 = cbase / cpg;
+            const uint32_t r0 = cbase - g0 * cpg;
             uint64_t w[UNROLL];
             float scale[UNROLL];
             Raw<DT> rm[UNROLL];
+            uint32_t cs[UNROLL];
             bool ok[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int64_t cs = cbase + u * kBlock + threadIdx.x;       // chunk within the sample
-                ok[u] = cs < a.cps;
-                w[u] = 0; scale[u] = 0.0f; rm[u] = zero_raw<DT>();
-                if (ok[u]) {
-                    w[u] = load_codes<BITS>(a.codes, out0 / kChunk + cs);
-                    scale[u] = scales_i[static_cast<uint32_t>(cs) / cpg];
-                    if (has_buf) rm[u] = load_raw<DT>(a.m_buf, m0 + cs * kChunk);
+                const uint32_t c = cbase + u * kBlock + threadIdx.x;       // chunk within the sample
+                ok[u] = c < cps;
+                cs[u] = ok[u] ? c : cps - 1;
+                const uint32_t x = r0 + (cs[u] - cbase);                   // < cpg + kStep
+                uint32_t dg;
+                if (cpg >= kStep) {
+                    dg = x >= cpg ? 1u : 0u;
+                } else {                                                   // x < 2^23: float is exact enough
+                    dg = static_cast<uint32_t>(static_cast<float>(x) * rcp_cpg);
+                    if (dg * cpg > x) --dg;
+                    else if ((dg + 1) * cpg <= x) ++dg;
                 }
+                w[u] = load_codes_at<BITS>(codes_s + static_cast<uint64_t>(cs[u]) * BITS);
+                scale[u] = scales_s[g0 + dg];
+                if constexpr (HAS_BUF) rm[u] = load_raw_at<DT>(m_s + static_cast<uint64_t>(cs[u]) * kChunkBytes);
             }
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const int64_t cs = cbase + u * kBlock + threadIdx.x;
-                const bool live = scale[u] != 0.0f;
-                const float step = (live ? scale[u] : 1.0f) / Levels<BITS>::half;
+                const GroupScale sc = scale_from_wire<BITS>(scale[u]);
                 int q[kChunk];
                 unpack_levels<BITS>(w[u], q);
-                float m_old[kChunk], m_new[kChunk];
-                unpack_raw<DT>(rm[u], m_old);
+                float dh[kChunk];
 #pragma unroll
-                for (int e = 0; e < kChunk; ++e) {
-                    const float dh = live ? value_of<BITS>(q[e], step) : 0.0f;
-                    m_new[e] = has_buf ? m_old[e] + dh : dh;
-                }
+                for (int e = 0; e < kChunk; ++e) dh[e] = value_of<BITS>(q[e], sc);
                 if (ok[u]) {
-                    const Raw<DT> packed = pack_raw<DT>(m_new);
-                    if (has_buf) store_raw<DT>(a.m_buf, m0 + cs * kChunk, packed);
-                    store_raw<DT>(a.out, out0 + cs * kChunk, packed);
+                    Raw<DT> packed;
+                    if constexpr (HAS_BUF) {
+                        packed = updated_chunk<DT>(rm[u], dh);
+                        store_raw_at<DT>(m_s + static_cast<uint64_t>(cs[u]) * kChunkBytes, packed);
+                    } else {
+                        packed = pack_raw<DT>(dh);
+                    }
+                    store_raw_at<DT>(out_s + static_cast<uint64_t>(cs[u]) * kChunkBytes, packed);
                 }
             }
         }
     }
+}
+
+template <int DT, int BITS, int UNROLL>
+__global__ __launch_bounds__(kBlock)
+void dequant_flat_kernel(const DequantArgs a) {
+    if (a.m_buf) dequant_flat_body<DT, BITS, UNROLL, true>(a);
+    else dequant_flat_body<DT, BITS, UNROLL, false>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -312,6 +366,31 @@ void dequant_anyshape_kernel(const DequantArgs a, const int bits) {
 // Launch tables, one set per dtype translation unit.
 // ---------------------------------------------------------------------------
 struct LaunchGeom { unsigned grid_x, grid_y; };
+
+// Optional timing of the next launch made by this host thread: when set (see
+// aqsgd_profile_next_launch) the kernel goes out through hipExtLaunchKernel,
+// which stamps the two events with the kernel's own start and end, and the
+// request is cleared.
+struct ProfileRequest { hipEvent_t start, stop; };
+extern thread_local ProfileRequest g_profile_request;
+
+template <typename... KArgs, typename... Args>
+hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
+                         Args... args) {
+    ProfileRequest& pr = g_profile_request;
+    if (pr.start || pr.stop) {
+        std::tuple<KArgs...> held(args...);
+        void* argv[sizeof...(KArgs)];
+        fill_arg_pointers(held, argv, std::index_sequence_for<KArgs...>{});
+        const hipError_t err = hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv,
+                                                  0, stream, pr.start, pr.stop, 0);
+        pr.start = nullptr;
+        pr.stop = nullptr;
+        return err;
+    }
+    hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
+    return hipGetLastError();
+}
 
 // Team shapes the dispatcher may pick; index into the table below.
 enum TeamShape {

@@ -137,6 +137,46 @@ def test_unchanged_activation_sends_zero_scale(H, dtype):
         assert int((scales == 0).sum()) == 3 * 16 - 1
 
 
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_tiny_magnitudes_keep_binary32_subnormals(H, bits):
+    """Groups whose max-abs sits around the 2^-120 floor: some are sent as zero,
+    the others have a level spacing that is a binary32 subnormal.  Nothing may be
+    flushed to zero on the way."""
+    import oracle
+    d = H.dev()
+    rng = np.random.default_rng(40 + bits)
+    n_per, G, N = 64 * 96, 64, 5
+    mag = np.repeat(10.0 ** rng.uniform(-37.5, -35.0, size=(3, n_per // G)), G, axis=1)
+    act_np = (rng.standard_normal((3, n_per)) * mag).astype(np.float32)
+    m_np = np.zeros((N, n_per), dtype=np.float32)
+    ids_np = np.array([4, 1, 2], dtype=np.int64)
+    m_send = torch.zeros((N, n_per), device=d)
+    m_recv = torch.zeros((N, n_per), device=d)
+    desc = B.make_desc(batch=3, n_per=n_per, n_samples=N, bits=bits, group=G, dtype="f32")
+    codes = torch.empty(B.codes_bytes(desc), dtype=torch.uint8, device=d)
+    scales = torch.empty(B.scales_count(desc), dtype=torch.float32, device=d)
+    out = torch.empty((3, n_per), device=d)
+    ids = torch.from_numpy(ids_np).to(d)
+    for visit in range(2):
+        a = (act_np * np.float32(1.0 + 0.25 * visit)).astype(np.float32)
+        B.encode(desc, torch.from_numpy(a).to(d), ids, m_send, codes, scales)
+        B.decode(desc, codes, scales, ids, m_recv, out)
+        wc, ws = oracle.encode(a, ids_np, m_np, dtype="f32", bits=bits, group=G)
+        torch.cuda.synchronize()
+        assert H.same_bytes(scales.cpu().numpy(), ws), H.first_diff(scales.cpu().numpy(), ws)
+        assert H.same_bytes(codes.cpu().numpy(), wc), H.first_diff(codes.cpu().numpy(), wc)
+        assert H.same_bytes(m_send.cpu().numpy(), m_np)
+        assert H.same_bytes(m_recv.cpu().numpy(), m_np)
+        assert H.same_bytes(out.cpu().numpy(), m_np[ids_np])
+        if visit == 0:
+            live = ws > 0
+            assert (~live).any() and live.any()
+            sub = (np.abs(a.reshape(-1, G)) < 2.0**-126) & (a.reshape(-1, G) != 0) & live[:, None]
+            assert sub.any()                                   # subnormal inputs in live groups
+            if bits == 8:                                      # and subnormal level spacings
+                assert (ws[live] / 127.5 < 2.0**-126).any()
+
+
 def test_check_ids_flags_duplicates_and_range(H):
     d = H.dev()
     for ids, want in [([0, 1, 2, 3], 0), ([0, 9, 2, 3], 1), ([0, 2, 2, 3], 2), ([-1, 5, 5, 1], 3)]:
