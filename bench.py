@@ -19,9 +19,17 @@ buffers are pre-seeded by one full pass and the activations then drift by
 
 The K timed steps are recorded into HIP graphs (256 steps each) and replayed
 back to back, bracketed by device synchronisation; wall time / K is ms_per_step.
-A second pass over the same K steps launches every kernel through the library's
-timed-launch hook, which stamps a HIP event pair with the kernel's own begin and
-end on its stream; those per-launch durations feed the roofline figure.
+Micro-batches touch disjoint samples and pool slots, so their codec calls are
+independent, as they are in a pipeline stage that has several micro-batches in
+flight: with --streams N (default 4) the forward pairs (encode then decode) are
+dealt round-robin over N/2 streams and the backward pairs over the other N/2, and
+a kernel's launch and completion latency overlaps other kernels' streaming.
+--streams 1 runs the four kernels of every step strictly one after the other.
+
+A further pass over the same K steps launches every kernel on its own, one after
+the other, through the library's timed-launch hook, which stamps a HIP event pair
+with the kernel's own begin and end on its stream; those per-launch durations feed
+the roofline figure (kernel quality), independent of how launches are overlapped.
 
 Prints ONE JSON line.
 """
@@ -49,10 +57,18 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
+    ap.add_argument("--streams", type=int, choices=[1, 2, 4, 8], default=4,
+                    help="1: the four kernels of a step run one after the other on one stream; "
+                         "N>1: N/2 streams carry forward pairs (encode then decode of one micro-batch) "
+                         "and N/2 carry backward pairs, micro-batches dealt round-robin; micro-batches "
+                         "touch disjoint samples and pool slots, so the chains are independent")
     ap.add_argument("--pool", type=int, default=96, help="micro-batch slots per rotating pool")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-calls", type=int, default=0, help="oracle sample size (0 = auto)")
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
+                         "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
     return ap.parse_args()
 
 
@@ -151,6 +167,30 @@ class Workload:
             self.grad_quant(k)
             self.grad_dequant(k)
 
+    def make_streams(self, count=4):
+        """Streams of the four roles of a boundary: the sending stage encodes
+        activations and reconstructs gradients, the receiving stage decodes
+        activations and quantises gradients.  Default priority everywhere."""
+        torch = self.torch
+        self.streams = [torch.cuda.Stream() for _ in range(count)]
+
+    def step_on_streams(self, k, backward=True):
+        """The same four launches as step(): the forward pair on one stream, the
+        backward pair on another; consecutive micro-batches take different streams."""
+        torch = self.torch
+        if not backward:
+            with torch.cuda.stream(self.streams[k % len(self.streams)]):
+                self.encode(k)
+                self.decode(k)
+            return
+        half = len(self.streams) // 2
+        with torch.cuda.stream(self.streams[k % half]):
+            self.encode(k)
+            self.decode(k)
+        with torch.cuda.stream(self.streams[half + k % half]):
+            self.grad_quant(k)
+            self.grad_dequant(k)
+
     # -- algorithmic bytes per launch (what the method must move) ----------------
     def leg_bytes(self):
         c = self.cfg
@@ -165,25 +205,44 @@ class Workload:
         }
 
 
-def timed_steps(wl, first, count, launch):
+def timed_steps(wl, first, count, launch, n_streams, backward=True):
     """Run `count` steps starting at step index `first`; returns wall seconds."""
     torch = wl.torch
+    main = torch.cuda.Stream()
+    if n_streams > 1:
+        wl.make_streams(n_streams)
+
+    def enqueue(k0, k1):
+        """Steps k0..k1-1 onto `main` (one stream) or fanned out from / joined back into it."""
+        if n_streams == 1:
+            for k in range(k0, k1):
+                wl.step(k, backward)
+            return
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for st in wl.streams:
+            st.wait_event(fork)
+        for k in range(k0, k1):
+            wl.step_on_streams(k, backward)
+        for st in wl.streams:
+            done = torch.cuda.Event()
+            done.record(st)
+            main.wait_event(done)
+
     if launch == "eager":
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for k in range(first, first + count):
-            wl.step(k)
+        with torch.cuda.stream(main):
+            enqueue(first, first + count)
         torch.cuda.synchronize()
         return time.perf_counter() - t0
     graphs = []
-    side = torch.cuda.Stream()
     k = first
     while k < first + count:
         m = min(GRAPH_STEPS, first + count - k)
         g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=side):
-            for j in range(k, k + m):
-                wl.step(j)
+        with torch.cuda.graph(g, stream=main):
+            enqueue(k, k + m)
         graphs.append(g)
         k += m
     torch.cuda.synchronize()
@@ -292,14 +351,25 @@ def main():
     wl.preseed_and_drift()
     t_setup = time.perf_counter() - t_setup
 
+    if args.calibration_copy:
+        src = torch.empty(1 << 29, dtype=torch.float16, device="cuda:0").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     for k in range(Wm):                                  # untimed warm-up, eager
         wl.step(k)
     torch.cuda.synchronize()
 
-    wall = timed_steps(wl, Wm, K, args.launch)
+    wall = timed_steps(wl, Wm, K, args.launch, args.streams)
     ms_per_step = wall / K * 1e3
     act_bytes = cfg.n * cfg.elem_bytes
     value = act_bytes / (wall / K) / 1e9
+
+    # forward messages alone (encode + decode of K micro-batches), same launch mode
+    fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False)
 
     legs = None if args.no_kernel_legs else kernel_legs(wl, Wm, K)
     lb = wl.leg_bytes()
@@ -316,13 +386,18 @@ def main():
                     "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch")}
         pair_us = legs["encode"]["avg_us"] + legs["decode"]["avg_us"]
         pair_bytes = lb["encode"] + lb["decode"]
-        extra["fwd_pair"] = {"us": round(pair_us, 3),
+        extra["fwd_pair_isolated_launches"] = {"us": round(pair_us, 3),
                              "act_GBps": round(act_bytes / pair_us / 1e3, 1),
                              "hbm_GBps": round(pair_bytes / pair_us / 1e3, 1),
                              "frac_of_hbm_peak": round(pair_bytes / pair_us / 1e3 / HBM_PEAK_GBPS, 4)}
         extra["kernels"] = {l: {"avg_us": round(legs[l]["avg_us"], 3),
                                 "median_us": round(legs[l]["median_us"], 3),
                                 "hbm_GBps": round(lb[l] / legs[l]["avg_us"] / 1e3, 1)} for l in wl.LEGS}
+    fwd_bytes = lb["encode"] + lb["decode"]
+    extra["fwd_only"] = {"us_per_microbatch": round(fwd_wall / K * 1e6, 3),
+                         "act_GBps": round(act_bytes / (fwd_wall / K) / 1e9, 1),
+                         "hbm_GBps": round(fwd_bytes / (fwd_wall / K) / 1e9, 1),
+                         "frac_of_hbm_peak": round(fwd_bytes / (fwd_wall / K) / 1e9 / HBM_PEAK_GBPS, 4)}
     step_bytes = sum(lb.values())
     extra["step_hbm_GBps"] = round(step_bytes / (wall / K) / 1e9, 1)
     extra["step_frac_of_hbm_peak"] = round(step_bytes / (wall / K) / 1e9 / HBM_PEAK_GBPS, 4)
@@ -345,7 +420,7 @@ def main():
                                "micro-batch / step time",
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
-                   "group": cfg.fwd_group, "pool_slots": args.pool, "launch": args.launch,
+                   "group": cfg.fwd_group, "pool_slots": args.pool, "launch": args.launch, "streams": args.streams,
                    "cold_buffers": True, "device": torch.cuda.get_device_name(0),
                    "setup_s": round(t_setup, 1)},
         "roofline": roofline, "cpu_baseline": base,

@@ -262,25 +262,28 @@ __device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint64_t j0, float
 // ---------------------------------------------------------------------------
 // Max over the TEAM consecutive lanes a lane belongs to (TEAM = 1..64, power of
 // two).  The first four steps are DPP lane permutations inside a 16-lane row;
-// the last two cross rows through ds_bpermute.  Max of non-negative floats is
-// exact and order-free, so any tree gives the same bits.
+// the last two cross rows through ds_bpermute.  The values are magnitudes, so
+// their bit patterns order like unsigned integers and the reduction runs on
+// those (an integer max has no NaN quieting to do and fuses with the DPP move).
+// Max is exact and order-free, so any tree gives the same bits.
 // ---------------------------------------------------------------------------
 template <int CTRL>
-__device__ __forceinline__ float dpp_max_step(float v) {
-    const int other = __builtin_amdgcn_update_dpp(__float_as_int(v), __float_as_int(v), CTRL,
-                                                  0xf, 0xf, false);
-    return __builtin_fmaxf(v, __int_as_float(other));
+__device__ __forceinline__ uint32_t dpp_max_step(uint32_t v) {
+    const uint32_t other = static_cast<uint32_t>(
+        __builtin_amdgcn_update_dpp(static_cast<int>(v), static_cast<int>(v), CTRL, 0xf, 0xf, false));
+    return max(v, other);
 }
 
 template <int TEAM>
-__device__ __forceinline__ float team_max(float v) {
+__device__ __forceinline__ float team_max(float magnitude) {
+    uint32_t v = __float_as_uint(magnitude);
     if constexpr (TEAM >= 2) v = dpp_max_step<0xB1>(v);     // quad_perm [1,0,3,2]
     if constexpr (TEAM >= 4) v = dpp_max_step<0x4E>(v);     // quad_perm [2,3,0,1]
     if constexpr (TEAM >= 8) v = dpp_max_step<0x141>(v);    // row_half_mirror
     if constexpr (TEAM >= 16) v = dpp_max_step<0x140>(v);   // row_mirror
-    if constexpr (TEAM >= 32) v = __builtin_fmaxf(v, __shfl_xor(v, 16, kWave));
-    if constexpr (TEAM >= 64) v = __builtin_fmaxf(v, __shfl_xor(v, 32, kWave));
-    return v;
+    if constexpr (TEAM >= 32) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 16, kWave)));
+    if constexpr (TEAM >= 64) v = max(v, static_cast<uint32_t>(__shfl_xor(static_cast<int>(v), 32, kWave)));
+    return __uint_as_float(v);
 }
 
 // ---------------------------------------------------------------------------
@@ -328,49 +331,90 @@ __device__ __forceinline__ GroupScale scale_from_wire(float s_tx) {
     return g;
 }
 
-// Level index of one value; r = 1/2 (nearest, ties upwards) or U[0,1).
-// y = ((d * inv) + L/2) + r is never below -2^-20, so converting towards zero is
-// floor() followed by the clamp at 0.  With r = 1/2, |d| <= s bounds y below
-// L + 1, so no upper clamp is needed; a stochastic r can reach L + 1.
+// Level of one value, kept as a float (an exact small integer); r = 1/2
+// (nearest, ties upwards) or U[0,1).
+// y = ((d * inv) + L/2) + r is never below -2^-20, so rounding towards zero is
+// floor() followed by the clamp at 0 (a result of -0 counts as level 0 in all
+// that follows).  With r = 1/2, |d| <= s bounds y below L + 1, so no upper clamp
+// is needed; a stochastic r can reach L + 1.
 template <int BITS, int ROUND>
-__device__ __forceinline__ int level_of(float d, const GroupScale& g, float r) {
+__device__ __forceinline__ float level_of(float d, const GroupScale& g, float r) {
     float t = d * g.inv;
     t = t + g.offset;
     const float y = t + r;
-    const int k = static_cast<int>(y);
-    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) return min(k, Levels<BITS>::top);
-    else return k;
+    const float k = __builtin_truncf(y);
+    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC)
+        return __builtin_fminf(k, static_cast<float>(Levels<BITS>::top));
+    else
+        return k;
 }
 
-template <int BITS>
-__device__ __forceinline__ float value_of(int k, const GroupScale& g) {
-    return (static_cast<float>(k) - g.offset) * g.step;
+__device__ __forceinline__ float value_of(float level, const GroupScale& g) {
+    return (level - g.offset) * g.step;
 }
 
 // Eight levels -> 8*BITS bits, element e at bits [e*BITS, e*BITS + BITS).
+// The levels are small integers held in floats, so up to 24 bits of the stream
+// are assembled exactly in binary32 (level * 2^shift added up: every partial sum
+// is an integer below 2^24) and converted once, instead of one conversion and
+// one shift-or per element.  Eight-bit levels go through v_cvt_pk_u8_f32, which
+// converts and places a byte in one step.
 template <int BITS>
-__device__ __forceinline__ uint64_t pack_levels(const int (&q)[kChunk]) {
+__device__ __forceinline__ uint64_t pack_levels(const float (&q)[kChunk]) {
     if constexpr (BITS == 8) {
         uint32_t lo = 0, hi = 0;
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
-            lo |= static_cast<uint32_t>(q[e]) << (8 * e);
-            hi |= static_cast<uint32_t>(q[4 + e]) << (8 * e);
+            lo = __builtin_amdgcn_cvt_pk_u8_f32(q[e], e, lo);
+            hi = __builtin_amdgcn_cvt_pk_u8_f32(q[4 + e], e, hi);
         }
         return (static_cast<uint64_t>(hi) << 32) | lo;
-    } else {
-        uint32_t w = 0;
+    } else if constexpr (BITS == 4) {
+        float lo = q[0], hi = q[4];
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) w |= static_cast<uint32_t>(q[e]) << (BITS * e);
-        return w;
+        for (int e = 1; e < 4; ++e) {
+            lo = __builtin_fmaf(q[e], static_cast<float>(1 << (4 * e)), lo);
+            hi = __builtin_fmaf(q[4 + e], static_cast<float>(1 << (4 * e)), hi);
+        }
+        return (static_cast<uint32_t>(hi) << 16) | static_cast<uint32_t>(lo);
+    } else {                                         // 2 or 3 bits: 16 or 24 bits in all
+        float w = q[0];
+#pragma unroll
+        for (int e = 1; e < kChunk; ++e) w = __builtin_fmaf(q[e], static_cast<float>(1 << (BITS * e)), w);
+        return static_cast<uint32_t>(w);
     }
 }
 
+// The inverse: eight levels as floats.
 template <int BITS>
-__device__ __forceinline__ void unpack_levels(uint64_t w, int (&q)[kChunk]) {
+__device__ __forceinline__ void unpack_levels(uint64_t w, float (&q)[kChunk]) {
+    if constexpr (BITS == 8) {
+        const uint32_t lo = static_cast<uint32_t>(w), hi = static_cast<uint32_t>(w >> 32);
 #pragma unroll
-    for (int e = 0; e < kChunk; ++e)
-        q[e] = static_cast<int>((w >> (BITS * e)) & static_cast<uint64_t>(Levels<BITS>::top));
+        for (int e = 0; e < 4; ++e) {
+            q[e] = static_cast<float>((lo >> (8 * e)) & 0xffu);         // v_cvt_f32_ubyteN
+            q[4 + e] = static_cast<float>((hi >> (8 * e)) & 0xffu);
+        }
+    } else if constexpr (BITS == 4) {
+        const uint32_t even = static_cast<uint32_t>(w) & 0x0f0f0f0fu;          // elements 0, 2, 4, 6
+        const uint32_t odd = (static_cast<uint32_t>(w) >> 4) & 0x0f0f0f0fu;    // elements 1, 3, 5, 7
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            q[2 * b] = static_cast<float>((even >> (8 * b)) & 0xffu);
+            q[2 * b + 1] = static_cast<float>((odd >> (8 * b)) & 0xffu);
+        }
+    } else if constexpr (BITS == 2) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {                // byte b of this word holds element 4*b + s
+            const uint32_t m = (static_cast<uint32_t>(w) >> (2 * s)) & 0x0303u;
+            q[s] = static_cast<float>(m & 0xffu);
+            q[4 + s] = static_cast<float>((m >> 8) & 0xffu);
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e)
+            q[e] = static_cast<float>((static_cast<uint32_t>(w) >> (BITS * e)) & Levels<BITS>::top);
+    }
 }
 
 // Codes of one chunk to / from the byte stream; chunk c of the call starts at

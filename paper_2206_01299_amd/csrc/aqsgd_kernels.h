@@ -90,6 +90,9 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
         if constexpr (HAS_BUF) rm[k] = load_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes);
         else rm[k] = zero_raw<DT>();
     }
+    // Keep all of the group's loads ahead of the first use: the scheduler would
+    // otherwise sink them next to their consumers and leave two or three in flight.
+    __builtin_amdgcn_sched_barrier(0);
 
     // ---- delta and the group's max-abs --------------------------------------------
     float d[CPL][kChunk];
@@ -120,12 +123,11 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
 #pragma unroll
             for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
         }
-        int q[kChunk];
-        float dh[kChunk];
+        float q[kChunk], dh[kChunk];
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
             q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[e]);
-            dh[e] = value_of<BITS>(q[e], sc);
+            dh[e] = value_of(q[e], sc);
         }
         store_codes_at<BITS>(codes_s + goff / kChunk * BITS + cc[k] * BITS, pack_levels<BITS>(q));
         if constexpr (HAS_BUF)
@@ -229,14 +231,14 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
                 scale[u] = scales_s[g0 + dg];
                 if constexpr (HAS_BUF) rm[u] = load_raw_at<DT>(m_s + static_cast<uint64_t>(cs[u]) * kChunkBytes);
             }
+            __builtin_amdgcn_sched_barrier(0);           // every load is out before the first use
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
                 const GroupScale sc = scale_from_wire<BITS>(scale[u]);
-                int q[kChunk];
+                float q[kChunk], dh[kChunk];
                 unpack_levels<BITS>(w[u], q);
-                float dh[kChunk];
 #pragma unroll
-                for (int e = 0; e < kChunk; ++e) dh[e] = value_of<BITS>(q[e], sc);
+                for (int e = 0; e < kChunk; ++e) dh[e] = value_of(q[e], sc);
                 if (ok[u]) {
                     Raw<DT> packed;
                     if constexpr (HAS_BUF) {
