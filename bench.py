@@ -51,6 +51,21 @@ HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E peak
 GRAPH_STEPS = 256               # steps recorded per HIP graph
 
 
+WORKLOAD_TEXT = {
+    "gpt2_4bit": "GPT2-1.5B-shaped stage boundary: float16 activations [4,1024,1600], 8192-sample "
+                 "float16 m_buf x2 (sender, receiver), forward 4-bit per-row delta codec, backward "
+                 "8-bit direct",
+    "gpt2_2bit_stochastic": "GPT2-1.5B-shaped stage boundary: float16 [4,1024,1600], 8192-sample m_buf "
+                            "x2, forward 2-bit delta with Philox stochastic rounding in groups of 128, "
+                            "backward 4-bit stochastic",
+    "deberta_3bit": "DeBERTa-1.5B-shaped stage boundary: bfloat16 activations [32,256,1536], "
+                    "100k-sample bfloat16 m_buf x2 (78.6 GB each), forward 3-bit delta in groups of 64, "
+                    "backward 8-bit",
+    "stress": "stress boundary: float32 activations [8,2048,4096] with outlier tokens, 256-sample "
+              "float32 m_buf x2, forward 4-bit per-row delta, backward 8-bit",
+}
+
+
 def parse_args():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -62,7 +77,12 @@ def parse_args():
                          "N>1: N/2 streams carry forward pairs (encode then decode of one micro-batch) "
                          "and N/2 carry backward pairs, micro-batches dealt round-robin; micro-batches "
                          "touch disjoint samples and pool slots, so the chains are independent")
-    ap.add_argument("--pool", type=int, default=96, help="micro-batch slots per rotating pool")
+    ap.add_argument("--pool", type=int, default=0,
+                    help="micro-batch slots per rotating pool (0 = enough for 1.25 GB per pool)")
+    ap.add_argument("--config", default="gpt2_4bit",
+                    choices=["gpt2_4bit", "gpt2_2bit_stochastic", "deberta_3bit", "stress"],
+                    help="workload; the default is the one the headline metric is quoted on, the "
+                         "others give secondary lines")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-calls", type=int, default=0, help="oracle sample size (0 = auto)")
@@ -96,11 +116,16 @@ class Workload:
         self.m_send = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
         self.m_recv = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
 
-        # channel outliers: 1 % of the hidden channels carry 20x the scale
-        chan = torch.ones(cfg.hidden, device=d)
+        # outliers: a fraction of the hidden channels, or of the token rows, carries a larger scale
+        chan = torch.ones((1, cfg.hidden), device=d)
         k = int(round(cfg.outlier_channel_frac * cfg.hidden))
         if k:
-            chan[torch.randperm(cfg.hidden, generator=g, device=d)[:k]] = cfg.outlier_scale
+            chan[0, torch.randperm(cfg.hidden, generator=g, device=d)[:k]] = cfg.outlier_scale
+        k = int(round(cfg.outlier_token_frac * cfg.seq))
+        if k:
+            tok = torch.ones((cfg.seq, 1), device=d)
+            tok[torch.randperm(cfg.seq, generator=g, device=d)[:k], 0] = cfg.outlier_scale
+            chan = chan * tok
         self.chan = chan
 
         shape = (pool, Bn, cfg.seq, cfg.hidden)
@@ -122,9 +147,19 @@ class Workload:
         torch.cuda.synchronize()
 
     def _draw(self, shape):
+        """fp32 draws of the configuration's law, on the device."""
         torch, c = self.torch, self.cfg
+        z = torch.randn(shape, device=self.dev, generator=self.gen)
         if c.law == "normal":
-            return torch.randn(shape, device=self.dev, generator=self.gen)
+            return z
+        if c.law == "student_t3":                  # z / sqrt(chi2_3 / 3)
+            chi = torch.zeros(shape, device=self.dev)
+            for _ in range(3):
+                chi += torch.randn(shape, device=self.dev, generator=self.gen) ** 2
+            return z / torch.sqrt(chi / 3.0)
+        if c.law == "laplace":                     # exponential magnitude, random sign
+            mag = torch.empty(shape, device=self.dev).exponential_(1.0, generator=self.gen)
+            return torch.where(z >= 0, mag, -mag)
         raise NotImplementedError(c.law)
 
     def preseed_and_drift(self):
@@ -142,6 +177,7 @@ class Workload:
     # -- the four launches of one step -----------------------------------------
     def encode(self, k):
         s = k % self.pool
+        self.fdesc.rng_seed = 0x5EED0000 + 2 * k           # a fresh key per message
         self.B.encode(self.fdesc, self.act[s], self.ids[k % self.calls], self.m_send,
                       self.codes[s], self.scales[s])
 
@@ -152,6 +188,7 @@ class Workload:
 
     def grad_quant(self, k):
         s = k % self.pool
+        self.bdesc.rng_seed = 0x5EED0001 + 2 * k
         self.B.grad_quant(self.bdesc, self.grad[s], self.bcodes[s], self.bscales[s])
 
     def grad_dequant(self, k):
@@ -344,8 +381,11 @@ def main():
     from paper_2206_01299_amd import workloads as W
     B.lib()
 
-    cfg = W.gpt2_4bit()
+    cfg = {"gpt2_4bit": W.gpt2_4bit, "gpt2_2bit_stochastic": W.gpt2_2bit_stochastic,
+           "deberta_3bit": W.deberta_3bit, "stress": W.stress}[args.config]()
     K, Wm = args.steps, args.warmup
+    if args.pool <= 0:
+        args.pool = max(4, -(-1_250_000_000 // (cfg.n * cfg.elem_bytes)))
     t_setup = time.perf_counter()
     wl = Workload(cfg, args.pool)
     wl.preseed_and_drift()
@@ -378,7 +418,7 @@ def main():
     if legs:
         dominant = max(wl.LEGS, key=lambda l: legs[l]["avg_us"])
         a_gbps = lb[dominant] / (legs[dominant]["avg_us"] * 1e-6) / 1e9
-        traffic = read_traffic()
+        traffic = read_traffic() if args.config == "gpt2_4bit" else None
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(a_gbps, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
                     "algorithmic_bytes_per_launch": lb[dominant],
@@ -413,11 +453,9 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "GPT2-1.5B-shaped stage boundary: float16 activations [4,1024,1600], "
-                               "8192-sample float16 m_buf x2 (sender, receiver), forward 4-bit "
-                               "per-row delta codec, backward 8-bit direct; one step = encode + "
-                               "decode + grad_quant + grad_dequant; value = activation bytes of one "
-                               "micro-batch / step time",
+        "config": {"workload": WORKLOAD_TEXT[args.config] + "; one step = encode + decode + grad_quant + "
+                               "grad_dequant; value = activation bytes of one micro-batch / step time",
+                   "name": cfg.name,
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
                    "group": cfg.fwd_group, "pool_slots": args.pool, "launch": args.launch, "streams": args.streams,
