@@ -35,21 +35,7 @@ template <> struct ElemBytes<AQSGD_F32> { static constexpr int value = 4; };
 template <int DT> struct Raw { u32x4_t v; };
 template <> struct Raw<AQSGD_F32> { f32x4_t lo, hi; };
 
-template <int DT>
-__device__ __forceinline__ Raw<DT> load_raw(const void* base, int64_t elem) {
-    Raw<DT> r;
-    if constexpr (DT == AQSGD_F32) {
-        const f32x4_t* p = reinterpret_cast<const f32x4_t*>(static_cast<const float*>(base) + elem);
-        r.lo = __builtin_nontemporal_load(p);
-        r.hi = __builtin_nontemporal_load(p + 1);
-    } else {
-        const u32x4_t* p = reinterpret_cast<const u32x4_t*>(static_cast<const uint16_t*>(base) + elem);
-        r.v = __builtin_nontemporal_load(p);
-    }
-    return r;
-}
-
-// Same, at a byte address.
+// One chunk from / to a byte address.
 template <int DT>
 __device__ __forceinline__ Raw<DT> load_raw_at(const char* p) {
     Raw<DT> r;
@@ -63,12 +49,16 @@ __device__ __forceinline__ Raw<DT> load_raw_at(const char* p) {
     return r;
 }
 
+// A float32 chunk is two 16-byte stores per lane, 32 bytes apart between lanes:
+// each instruction fills half of every cache line.  Streaming (nontemporal)
+// stores of that shape reach 2.4 TB/s, ordinary stores, which L2 merges, 6.6;
+// the contiguous 16-byte-per-lane stores of the 16-bit types stream at full rate.
 template <int DT>
 __device__ __forceinline__ void store_raw_at(char* p, const Raw<DT>& r) {
     if constexpr (DT == AQSGD_F32) {
         f32x4_t* q = reinterpret_cast<f32x4_t*>(p);
-        __builtin_nontemporal_store(r.lo, q);
-        __builtin_nontemporal_store(r.hi, q + 1);
+        q[0] = r.lo;
+        q[1] = r.hi;
     } else {
         __builtin_nontemporal_store(r.v, reinterpret_cast<u32x4_t*>(p));
     }
@@ -82,18 +72,6 @@ __device__ __forceinline__ Raw<DT> zero_raw() {
     return r;
 }
 
-template <int DT>
-__device__ __forceinline__ void store_raw(void* base, int64_t elem, const Raw<DT>& r) {
-    if constexpr (DT == AQSGD_F32) {
-        f32x4_t* p = reinterpret_cast<f32x4_t*>(static_cast<float*>(base) + elem);
-        __builtin_nontemporal_store(r.lo, p);
-        __builtin_nontemporal_store(r.hi, p + 1);
-    } else {
-        u32x4_t* p = reinterpret_cast<u32x4_t*>(static_cast<uint16_t*>(base) + elem);
-        __builtin_nontemporal_store(r.v, p);
-    }
-}
-
 __device__ __forceinline__ float bf16_bits_to_f32(uint32_t b) { return __uint_as_float(b << 16); }
 
 // binary32 -> bfloat16, round to nearest even (the top 16 bits of the pattern,
@@ -102,6 +80,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float x) {
     uint32_t u = __float_as_uint(x);
     if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;   // NaN stays NaN
     return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// Two binary32 -> two bfloat16 in one register with gfx950's packed convert (round
+// to nearest even; checked equal to f32_to_bf16_bits on all 2^32 inputs).
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2(float lo, float hi) {
+    uint32_t r;
+    asm("v_cvt_pk_bf16_f32 %0, %1, %2" : "=v"(r) : "v"(lo), "v"(hi));
+    return r;
 }
 
 template <int DT>
@@ -135,8 +121,7 @@ __device__ __forceinline__ Raw<DT> pack_raw(const float (&f)[kChunk]) {
         r.v = __builtin_bit_cast(u32x4_t, h);
     } else {
 #pragma unroll
-        for (int e = 0; e < 4; ++e)
-            r.v[e] = f32_to_bf16_bits(f[2 * e]) | (f32_to_bf16_bits(f[2 * e + 1]) << 16);
+        for (int e = 0; e < 4; ++e) r.v[e] = f32x2_to_bf16x2(f[2 * e], f[2 * e + 1]);
     }
     return r;
 }
@@ -415,6 +400,28 @@ __device__ __forceinline__ void unpack_levels(uint64_t w, float (&q)[kChunk]) {
         for (int e = 0; e < kChunk; ++e)
             q[e] = static_cast<float>((static_cast<uint32_t>(w) >> (BITS * e)) & Levels<BITS>::top);
     }
+}
+
+// Three-bit codes: a chunk is 3 bytes, so four neighbouring lanes own 12 bytes =
+// three aligned dwords.  Lane j of the quad (j < 3) assembles dword j from its own
+// 24 bits and the next lane's (one DPP quad permute), which turns three byte
+// stores per lane into one dword store for three lanes out of four.  `w` holds the
+// lane's 24 code bits; `quad_base` points at the first byte of the quad's 12.
+__device__ __forceinline__ void store_codes3_quad(uint8_t* quad_base, uint32_t w, int j, bool live) {
+    const uint32_t next = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+        0, static_cast<int>(w), 0xF9 /* quad_perm [1,2,3,3] */, 0xf, 0xf, false));
+    const uint32_t word = (w >> (8 * j)) | (next << (24 - 8 * j));     // j = 0, 1, 2
+    if (live && j < 3) reinterpret_cast<uint32_t*>(quad_base)[j] = word;
+}
+
+// The inverse: lanes 0..2 of the quad load one dword each, every lane rebuilds its
+// own 24 bits from its dword and the previous lane's.
+__device__ __forceinline__ uint32_t load_codes3_quad(const uint8_t* quad_base, int j) {
+    const uint32_t cur = j < 3 ? reinterpret_cast<const uint32_t*>(quad_base)[j] : 0u;
+    const uint32_t prev = static_cast<uint32_t>(__builtin_amdgcn_update_dpp(
+        0, static_cast<int>(cur), 0x90 /* quad_perm [0,0,1,2] */, 0xf, 0xf, false));
+    const uint64_t both = (static_cast<uint64_t>(cur) << 32) | prev;   // lane j starts at bit 32 - 8j
+    return static_cast<uint32_t>(both >> (32 - 8 * j)) & 0xffffffu;
 }
 
 // Codes of one chunk to / from the byte stream; chunk c of the call starts at

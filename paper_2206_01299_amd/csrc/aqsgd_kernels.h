@@ -129,7 +129,15 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
             q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[e]);
             dh[e] = value_of(q[e], sc);
         }
-        store_codes_at<BITS>(codes_s + goff / kChunk * BITS + cc[k] * BITS, pack_levels<BITS>(q));
+        uint8_t* group_codes = codes_s + goff / kChunk * BITS;
+        if (BITS == 3 && TEAM % 4 == 0 && a.cpg % 4 == 0) {
+            // whole quads of lanes are inside the group or past its end
+            const bool inside = k * TEAM + lane_in_team < a.cpg;
+            store_codes3_quad(group_codes + (cc[k] & ~3u) * 3, static_cast<uint32_t>(pack_levels<BITS>(q)),
+                              lane_in_team & 3, inside);
+        } else {
+            store_codes_at<BITS>(group_codes + cc[k] * BITS, pack_levels<BITS>(q));
+        }
         if constexpr (HAS_BUF)
             store_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes, updated_chunk<DT>(rm[k], dh));
     }
@@ -227,7 +235,10 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
                     if (dg * cpg > x) --dg;
                     else if ((dg + 1) * cpg <= x) ++dg;
                 }
-                w[u] = load_codes_at<BITS>(codes_s + static_cast<uint64_t>(cs[u]) * BITS);
+                if (BITS == 3 && cps % 4 == 0)           // quads of lanes never straddle the end
+                    w[u] = load_codes3_quad(codes_s + static_cast<uint64_t>(cs[u] & ~3u) * 3, threadIdx.x & 3);
+                else
+                    w[u] = load_codes_at<BITS>(codes_s + static_cast<uint64_t>(cs[u]) * BITS);
                 scale[u] = scales_s[g0 + dg];
                 if constexpr (HAS_BUF) rm[u] = load_raw_at<DT>(m_s + static_cast<uint64_t>(cs[u]) * kChunkBytes);
             }
