@@ -128,6 +128,22 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
                        void* out, void* stream);
 
 /*
+ * Uncompressed first visit (Algorithm 1: "if xi not seen before: set m(xi) = a(xi)";
+ * Appendix D runs a whole warm-up epoch this way): the message is the activation
+ * itself, at full precision, and both stages store it as m(xi).
+ *     m_buf[sample_ids[i]] <- act[i]        for every sample i of the call
+ * The sender calls it with its activation, the receiver with the activation it
+ * received, which keeps the two copies identical.  A later aqsgd_encode of the same
+ * activation finds a zero change.  Only batch, n_per, n_samples and dtype of the
+ * descriptor are used; bits, group and rounding are ignored (but must be valid).
+ *   act         in   [batch, n_per]
+ *   sample_ids  in   int64[batch], distinct, each in [0, n_samples)
+ *   m_buf       i/o  [n_samples, n_per]
+ */
+int aqsgd_seed(const aqsgd_desc* desc, const void* act, const int64_t* sample_ids,
+               void* m_buf, void* stream);
+
+/*
  * Debug helper: checks on the device that sample_ids are distinct and in range.
  * `flag` is one device int32 the caller has zeroed; the kernel sets bit 0 if an id
  * is out of range and bit 1 if two ids are equal.  O(batch^2) comparisons.

@@ -71,6 +71,8 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_oracle_dequantize_group.argtypes = [vp, ctypes.c_float, i64, i32, vp]
         L.aqsgd_oracle_encode.restype = i32
         L.aqsgd_oracle_encode.argtypes = [i32, i32, i64, i32, u64, i64, i64, vp, vp, vp, vp, vp]
+        L.aqsgd_oracle_seed.restype = i32
+        L.aqsgd_oracle_seed.argtypes = [i32, i64, i64, vp, vp, vp]
         L.aqsgd_oracle_decode.restype = i32
         L.aqsgd_oracle_decode.argtypes = [i32, i32, i64, i64, i64, vp, vp, vp, vp, vp]
         L.aqsgd_oracle_grad_quant.restype = i32
@@ -193,6 +195,23 @@ def encode(act: np.ndarray, ids: np.ndarray, m_buf: np.ndarray, *, dtype: str, b
     if rc:
         raise ValueError(f"oracle encode rejected its arguments (rc={rc})")
     return codes, scales
+
+
+def seed(act: np.ndarray, ids: np.ndarray, m_buf: np.ndarray, *, dtype: str) -> None:
+    """Uncompressed first visit: ``m_buf[ids] <- act`` in place."""
+    dt = DTYPE_CODE[dtype]
+    _check(act, _NP_OF[dt], "act"); _check(m_buf, _NP_OF[dt], "m_buf")
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    batch = ids.size
+    assert m_buf.ndim >= 2, "m_buf must be [rows, ...sample shape]"
+    n_rows = m_buf.shape[0]
+    n_per = m_buf.size // n_rows
+    assert act.size == batch * n_per
+    assert batch == 0 or (ids.min() >= 0 and ids.max() < n_rows), "sample id out of range"
+    assert len(np.unique(ids)) == batch, "duplicate sample ids in one call"
+    rc = lib().aqsgd_oracle_seed(dt, batch, n_per, _ptr(act), _ptr(ids), _ptr(m_buf))
+    if rc:
+        raise ValueError(f"oracle seed rejected its arguments (rc={rc})")
 
 
 def decode(codes: np.ndarray, scales: np.ndarray, ids: np.ndarray, m_buf: np.ndarray, *,

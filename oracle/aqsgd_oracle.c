@@ -315,6 +315,23 @@ int aqsgd_oracle_encode(int dtype, int bits, int64_t group, int rounding, uint64
 }
 
 /* ------------------------------------------------------------------ */
+/* Uncompressed first visit (Algorithm 1: "if xi not seen before, set  */
+/* m(xi) = a(xi)"; Appendix D's warm-up epoch): the row is the          */
+/* activation, bit for bit, on whichever machine calls it.              */
+/* ------------------------------------------------------------------ */
+int aqsgd_oracle_seed(int dtype, int64_t batch, int64_t n_per, const void* act,
+                      const int64_t* ids, void* m_buf)
+{
+    if (dtype < 0 || dtype > 2 || batch < 0 || n_per <= 0) return -1;
+    const size_t eb = dtype == ORACLE_F32 ? 4 : 2;
+    for (int64_t i = 0; i < batch; ++i)
+        for (int64_t e = 0; e < n_per; ++e)
+            memcpy((char*)m_buf + ((size_t)ids[i] * n_per + e) * eb,
+                   (const char*)act + ((size_t)i * n_per + e) * eb, eb);
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
 /* Receiver: m <- m + Delta m on its own replica; the updated m is the */
 /* activation the next stage consumes.                                 */
 /* ------------------------------------------------------------------ */

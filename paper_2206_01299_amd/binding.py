@@ -22,7 +22,7 @@ DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
-           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_check_ids",
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_check_ids",
            "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
@@ -64,6 +64,8 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_grad_quant.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_grad_dequant.restype = ctypes.c_int
         L.aqsgd_grad_dequant.argtypes = [dp, vp, vp, vp, vp]
+        L.aqsgd_seed.restype = ctypes.c_int
+        L.aqsgd_seed.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_check_ids.restype = ctypes.c_int
         L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
         L.aqsgd_profile_next_launch.restype = ctypes.c_int
@@ -136,6 +138,12 @@ def grad_quant(desc: Desc, grad, codes, scales, stream=None) -> None:
 def grad_dequant(desc: Desc, codes, scales, out, stream=None) -> None:
     _raise(lib().aqsgd_grad_dequant(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
                                     _dev(out, "out"), _stream(stream)))
+
+
+def seed(desc: Desc, act, sample_ids, m_buf, stream=None) -> None:
+    """``aqsgd_seed``: uncompressed first visit, ``m_buf[sample_ids] <- act``."""
+    _raise(lib().aqsgd_seed(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
+                            _dev(m_buf, "m_buf"), _stream(stream)))
 
 
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:

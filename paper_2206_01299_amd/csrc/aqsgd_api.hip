@@ -171,6 +171,32 @@ int run_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
+// Row copy for the uncompressed first visit: 16 bytes per lane and step, streaming.
+__global__ __launch_bounds__(kBlock)
+void seed_rows_kernel(const char* act, const int64_t* ids, char* m_buf, int64_t row_bytes, int batch) {
+    const int64_t n16 = row_bytes / 16;
+    for (int i = blockIdx.y; i < batch; i += gridDim.y) {
+        const u32x4_t* src = reinterpret_cast<const u32x4_t*>(act + static_cast<int64_t>(i) * row_bytes);
+        u32x4_t* dst = reinterpret_cast<u32x4_t*>(m_buf + ids[i] * row_bytes);
+        for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < n16;
+             c += static_cast<int64_t>(gridDim.x) * kBlock)
+            __builtin_nontemporal_store(__builtin_nontemporal_load(src + c), dst + c);
+    }
+}
+
+// Same for rows whose size is not a multiple of 16 bytes: element by element.
+template <typename T>
+__global__ __launch_bounds__(kBlock)
+void seed_rows_elem_kernel(const T* act, const int64_t* ids, T* m_buf, int64_t n_per, int batch) {
+    for (int i = blockIdx.y; i < batch; i += gridDim.y) {
+        const T* src = act + static_cast<int64_t>(i) * n_per;
+        T* dst = m_buf + ids[i] * n_per;
+        for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < n_per;
+             c += static_cast<int64_t>(gridDim.x) * kBlock)
+            dst[c] = src[c];
+    }
+}
+
 __global__ void check_ids_kernel(const int64_t* ids, int64_t batch, int64_t n_samples, int32_t* flag) {
     int bad = 0;
     for (int64_t i = threadIdx.x + static_cast<int64_t>(blockIdx.x) * blockDim.x; i < batch;
@@ -252,6 +278,36 @@ int aqsgd_grad_dequant(const aqsgd_desc* d, const uint8_t* codes, const float* s
     const bool flat = n <= (int64_t{1} << 34);
     return run_dequant(d, flat ? 1 : d->batch, flat ? n : d->n_per, codes, scales, nullptr, nullptr, out,
                        static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_seed(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
+               void* stream) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!act || !sample_ids || !m_buf) return AQSGD_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(sample_ids, 8)) return AQSGD_ERR_ALIGN;
+    const int64_t eb = d->dtype == AQSGD_F32 ? 4 : 2;
+    const int64_t row_bytes = d->n_per * eb;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t err;
+    if (row_bytes % 16 == 0) {
+        err = launch_kernel(seed_rows_kernel, dim3(geometry(row_bytes / 16, kBlock * 2, d->batch).grid_x,
+                                                   geometry(row_bytes / 16, kBlock * 2, d->batch).grid_y),
+                            dim3(kBlock), s, static_cast<const char*>(act), sample_ids,
+                            static_cast<char*>(m_buf), row_bytes, static_cast<int>(d->batch));
+    } else {
+        const LaunchGeom g = geometry(d->n_per, kBlock * 4, d->batch);
+        if (eb == 4)
+            err = launch_kernel(seed_rows_elem_kernel<uint32_t>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
+                                static_cast<const uint32_t*>(act), sample_ids, static_cast<uint32_t*>(m_buf),
+                                d->n_per, static_cast<int>(d->batch));
+        else
+            err = launch_kernel(seed_rows_elem_kernel<uint16_t>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
+                                static_cast<const uint16_t*>(act), sample_ids, static_cast<uint16_t*>(m_buf),
+                                d->n_per, static_cast<int>(d->batch));
+    }
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
 int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples, int32_t* flag,

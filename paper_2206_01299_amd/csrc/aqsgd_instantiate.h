@@ -9,7 +9,7 @@ namespace aqsgd {
 
 template <int DT, int BITS, int ROUND, int TEAM, int CPL>
 static hipError_t launch_qt(LaunchGeom g, const QuantArgs& a, hipStream_t stream) {
-    constexpr int threads = TEAM > kBlock ? TEAM : kBlock;
+    constexpr int threads = TEAM > kWave ? TEAM : kBlock;
     return launch_kernel(quant_team_kernel<DT, BITS, ROUND, TEAM, CPL>, dim3(g.grid_x, g.grid_y),
                          dim3(threads), stream, a);
 }

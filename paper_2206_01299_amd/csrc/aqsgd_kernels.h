@@ -77,7 +77,7 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
                                                  int64_t g, const uint32_t (&cc)[CPL],
                                                  int lane_in_team, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
-    constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
 
@@ -147,7 +147,7 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
 template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
 __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
-    constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
     constexpr int kEB = ElemBytes<DT>::value;
 
@@ -182,9 +182,9 @@ __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_
 }
 
 template <int DT, int BITS, int ROUND, int TEAM, int CPL>
-__global__ __launch_bounds__((TEAM > kBlock ? TEAM : kBlock))
+__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
 void quant_team_kernel(const QuantArgs a) {
-    constexpr int kThreads = TEAM > kBlock ? TEAM : kBlock;
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     static_assert(TEAM <= kWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
     [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
     if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, wave_max);

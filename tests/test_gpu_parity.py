@@ -177,6 +177,42 @@ def test_tiny_magnitudes_keep_binary32_subnormals(H, bits):
                 assert (ws[live] / 127.5 < 2.0**-126).any()
 
 
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("n_per", [4096, 1001, 24])        # 16-byte rows and ragged rows
+def test_seed_then_encode_follows_algorithm_1(H, dtype, n_per):
+    """Uncompressed first visit on both sides, then a compressed second visit."""
+    import oracle
+    d = H.dev()
+    rng = np.random.default_rng(7 + n_per)
+    N, Bn = 9, 4
+    ids_np = np.array([8, 0, 3, 5], dtype=np.int64)
+    a0 = W.to_storage(rng.standard_normal((Bn, n_per)).astype(np.float32), dtype)
+    a1 = W.to_storage(W.storage_to_f32(a0, dtype) + 0.05 * rng.standard_normal((Bn, n_per)).astype(np.float32), dtype)
+    m_host = W.to_storage(rng.standard_normal((N, n_per)).astype(np.float32), dtype)   # stale contents
+    m_send = W.to_torch(m_host.copy(), dtype, d)
+    m_recv = W.to_torch(m_host.copy(), dtype, d)
+    ids = torch.from_numpy(ids_np).to(d)
+    desc = B.make_desc(batch=Bn, n_per=n_per, n_samples=N, bits=8, group=1, dtype=dtype)
+    B.seed(desc, W.to_torch(a0, dtype, d), ids, m_send)
+    B.seed(desc, W.to_torch(a0, dtype, d), ids, m_recv)
+    oracle.seed(a0, ids_np, m_host, dtype=dtype)
+    torch.cuda.synchronize()
+    assert H.same_bytes(W.from_torch(m_send, dtype), m_host)
+    assert H.same_bytes(W.from_torch(m_recv, dtype), m_host)
+    # second visit through the codec
+    codes = torch.empty(B.codes_bytes(desc), dtype=torch.uint8, device=d)
+    scales = torch.empty(B.scales_count(desc), dtype=torch.float32, device=d)
+    out = torch.empty((Bn, n_per), dtype=B.DTYPE_NAME[dtype], device=d)
+    B.encode(desc, W.to_torch(a1, dtype, d), ids, m_send, codes, scales)
+    B.decode(desc, codes, scales, ids, m_recv, out)
+    wc, ws = oracle.encode(a1, ids_np, m_host, dtype=dtype, bits=8, group=1)
+    torch.cuda.synchronize()
+    assert H.same_bytes(codes.cpu().numpy(), wc) and H.same_bytes(scales.cpu().numpy(), ws)
+    assert H.same_bytes(W.from_torch(m_send, dtype), m_host)
+    assert H.same_bytes(W.from_torch(m_recv, dtype), m_host)
+    assert H.same_bytes(W.from_torch(out, dtype), m_host[ids_np])
+
+
 def test_check_ids_flags_duplicates_and_range(H):
     d = H.dev()
     for ids, want in [([0, 1, 2, 3], 0), ([0, 9, 2, 3], 1), ([0, 2, 2, 3], 2), ([-1, 5, 5, 1], 3)]:

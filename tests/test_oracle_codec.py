@@ -264,3 +264,44 @@ def test_empty_call(oracle):
     codes, scales = oracle.encode(np.zeros((0, 64), np.float32), np.zeros(0, np.int64), m,
                                   dtype="f32", bits=4, group=64)
     assert codes.size == 0 and scales.size == 0 and np.all(m == 1)
+
+
+# ---------------------------------------------------------------------------
+# uncompressed first visit (Algorithm 1, lines "if xi not seen before")
+# ---------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", DTYPES)
+def test_seed_sets_m_to_the_activation(oracle, dtype):
+    rng = np.random.default_rng(21)
+    m = _rand_act(rng, (6, 200), dtype)
+    before = m.copy()
+    act = _rand_act(rng, (3, 200), dtype)
+    ids = np.array([4, 0, 5], dtype=np.int64)
+    oracle.seed(act, ids, m, dtype=dtype)
+    assert np.array_equal(m[ids].view(np.uint8), act.view(np.uint8))
+    rest = [1, 2, 3]
+    assert np.array_equal(m[rest].view(np.uint8), before[rest].view(np.uint8))
+    # the message error of a seeded sample is zero (used at the start of the proof of
+    # Theorem 3.1): encoding the same activation again sends nothing
+    codes, scales = oracle.encode(act.reshape(3, 200), ids, m, dtype=dtype, bits=4, group=8)
+    assert not scales.any() and not codes.any()
+    assert np.array_equal(W.storage_to_f32(m[ids], dtype), W.storage_to_f32(act, dtype))
+
+
+def test_seeded_start_beats_zero_start_on_the_second_visit(oracle):
+    """Algorithm 1 (full-precision first visit) against an all-zero m: after the
+    seed, the second visit quantises only the drift, so its error is far smaller
+    than what direct quantisation of the first visit leaves behind."""
+    cfg = W.tiny().scaled(n_samples=8, seq=16, hidden=64, fwd_group=64, fwd_bits=2)
+    stream = W.ActivationStream(cfg)
+    ids = stream.epoch_ids(0)[0]
+    a0 = stream.activations(ids, 0).reshape(cfg.batch, -1)
+    a1 = stream.activations(ids, 1).reshape(cfg.batch, -1)
+    m_seed = np.zeros((cfg.n_samples, cfg.n_per), dtype=np.float32)
+    m_zero = np.zeros_like(m_seed)
+    oracle.seed(a0, ids, m_seed, dtype="f32")
+    oracle.encode(a0, ids, m_zero, dtype="f32", bits=2, group=64)
+    oracle.encode(a1, ids, m_seed, dtype="f32", bits=2, group=64)
+    oracle.encode(a1, ids, m_zero, dtype="f32", bits=2, group=64)
+    err_seed = np.abs(m_seed[ids] - a1).mean()
+    err_zero = np.abs(m_zero[ids] - a1).mean()
+    assert err_seed < err_zero / 5
