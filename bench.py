@@ -60,7 +60,7 @@ WORKLOAD_TEXT = {
                             "backward 4-bit stochastic",
     "deberta_3bit": "DeBERTa-1.5B-shaped stage boundary: bfloat16 activations [32,256,1536], "
                     "100k-sample bfloat16 m_buf x2 (78.6 GB each), forward 3-bit delta in groups of 64, "
-                    "backward 8-bit",
+                    "backward 6-bit",
     "stress": "stress boundary: float32 activations [8,2048,4096] with outlier tokens, 256-sample "
               "float32 m_buf x2, forward 4-bit per-row delta, backward 8-bit",
 }

@@ -61,7 +61,7 @@ typedef enum { AQSGD_ROUND_NEAREST = 0, AQSGD_ROUND_STOCHASTIC = 1 } aqsgd_round
 typedef enum {
     AQSGD_OK = 0,
     AQSGD_ERR_NULL = -1,      /* a required pointer is NULL                         */
-    AQSGD_ERR_BITS = -2,      /* bits not in {2, 3, 4, 8}                           */
+    AQSGD_ERR_BITS = -2,      /* bits not in {2, 3, 4, 6, 8}                        */
     AQSGD_ERR_GROUP = -3,     /* group <= 0, n_per % group != 0, (group*bits) % 8   */
     AQSGD_ERR_DTYPE = -4,     /* unknown dtype or rounding mode                     */
     AQSGD_ERR_SHAPE = -5,     /* negative or overflowing batch / n_per / n_samples  */
@@ -74,7 +74,7 @@ typedef struct {
     int64_t batch;        /* B: samples in this call (0 is allowed: nothing happens) */
     int64_t n_per;        /* elements per sample (sequence length * hidden size)     */
     int64_t n_samples;    /* N: rows of m_buf; ignored by the two grad calls         */
-    int32_t bits;         /* b in {2, 3, 4, 8}                                       */
+    int32_t bits;         /* b in {2, 3, 4, 6, 8}                                    */
     int32_t group;        /* G: elements per scale                                   */
     int32_t dtype;        /* aqsgd_dtype of act / grad / m_buf / out                 */
     int32_t rounding;     /* aqsgd_round; decode and grad_dequant ignore it          */

@@ -207,13 +207,13 @@ void aqsgd_oracle_unpack(const uint8_t* bytes, int64_t count, int bits, int32_t*
 /*            U[0,1) draws for stochastic rounding                     */
 /* Out: level indices q in [0, 2^b-1], transmitted scale, Q(d).        */
 /* ------------------------------------------------------------------ */
-static float half_levels(int bits) { return (float)((1 << bits) - 1) / 2.0f; }
+static float half_levels(int bits) { return (float)((1 << bits) - 1) / 2.0f; }  /* exact */
 
 void aqsgd_oracle_quantize_group(const float* d, const float* r, int64_t G, int bits,
                                  int32_t* q, float* scale_out, float* dhat)
 {
     const int L = (1 << bits) - 1;       /* index of the top level */
-    const float hL = half_levels(bits);  /* 1.5, 3.5, 7.5, 127.5: exact */
+    const float hL = half_levels(bits);  /* 1.5, 3.5, 7.5, 31.5, 127.5: exact */
 
     float s = 0.0f;                      /* normaliser: max |d| over the group */
     for (int64_t e = 0; e < G; ++e) {
@@ -264,7 +264,7 @@ static int check_shape(int dtype, int bits, int64_t group, int rounding,
                        int64_t batch, int64_t n_per)
 {
     if (dtype < 0 || dtype > 2) return -1;
-    if (!(bits == 2 || bits == 3 || bits == 4 || bits == 8)) return -2;
+    if (!(bits == 2 || bits == 3 || bits == 4 || bits == 6 || bits == 8)) return -2;
     if (group <= 0 || n_per <= 0 || n_per % group) return -3;
     if ((group * bits) % 8) return -3;
     if (rounding != ORACLE_NEAREST && rounding != ORACLE_STOCHASTIC) return -4;

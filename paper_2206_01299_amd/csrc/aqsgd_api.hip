@@ -84,7 +84,7 @@ int check_desc(const aqsgd_desc* d, bool needs_buffer) {
     if (!d) return AQSGD_ERR_NULL;
     if (d->dtype != AQSGD_F32 && d->dtype != AQSGD_F16 && d->dtype != AQSGD_BF16) return AQSGD_ERR_DTYPE;
     if (d->rounding != AQSGD_ROUND_NEAREST && d->rounding != AQSGD_ROUND_STOCHASTIC) return AQSGD_ERR_DTYPE;
-    if (!(d->bits == 2 || d->bits == 3 || d->bits == 4 || d->bits == 8)) return AQSGD_ERR_BITS;
+    if (!(d->bits == 2 || d->bits == 3 || d->bits == 4 || d->bits == 6 || d->bits == 8)) return AQSGD_ERR_BITS;
     if (d->batch < 0 || d->n_per <= 0) return AQSGD_ERR_SHAPE;
     if (d->group <= 0 || d->n_per % d->group != 0) return AQSGD_ERR_GROUP;
     if ((static_cast<int64_t>(d->group) * d->bits) % 8 != 0) return AQSGD_ERR_GROUP;
@@ -332,7 +332,7 @@ const char* aqsgd_strerror(int status) {
     switch (status) {
     case AQSGD_OK:         return "ok";
     case AQSGD_ERR_NULL:   return "a required pointer is NULL";
-    case AQSGD_ERR_BITS:   return "bits must be 2, 3, 4 or 8";
+    case AQSGD_ERR_BITS:   return "bits must be 2, 3, 4, 6 or 8";
     case AQSGD_ERR_GROUP:  return "group must be positive, divide n_per, and hold whole bytes of codes";
     case AQSGD_ERR_DTYPE:  return "unknown dtype or rounding mode";
     case AQSGD_ERR_SHAPE:  return "batch / n_per / n_samples negative, zero or too large";

@@ -354,14 +354,14 @@ __device__ __forceinline__ uint64_t pack_levels(const float (&q)[kChunk]) {
             hi = __builtin_amdgcn_cvt_pk_u8_f32(q[4 + e], e, hi);
         }
         return (static_cast<uint64_t>(hi) << 32) | lo;
-    } else if constexpr (BITS == 4) {
+    } else if constexpr (BITS == 4 || BITS == 6) {  // two halves of 16 or 24 bits
         float lo = q[0], hi = q[4];
 #pragma unroll
         for (int e = 1; e < 4; ++e) {
-            lo = __builtin_fmaf(q[e], static_cast<float>(1 << (4 * e)), lo);
-            hi = __builtin_fmaf(q[4 + e], static_cast<float>(1 << (4 * e)), hi);
+            lo = __builtin_fmaf(q[e], static_cast<float>(1 << (BITS * e)), lo);
+            hi = __builtin_fmaf(q[4 + e], static_cast<float>(1 << (BITS * e)), hi);
         }
-        return (static_cast<uint32_t>(hi) << 16) | static_cast<uint32_t>(lo);
+        return (static_cast<uint64_t>(static_cast<uint32_t>(hi)) << (4 * BITS)) | static_cast<uint32_t>(lo);
     } else {                                         // 2 or 3 bits: 16 or 24 bits in all
         float w = q[0];
 #pragma unroll
@@ -394,6 +394,13 @@ __device__ __forceinline__ void unpack_levels(uint64_t w, float (&q)[kChunk]) {
             const uint32_t m = (static_cast<uint32_t>(w) >> (2 * s)) & 0x0303u;
             q[s] = static_cast<float>(m & 0xffu);
             q[4 + s] = static_cast<float>((m >> 8) & 0xffu);
+        }
+    } else if constexpr (BITS == 6) {
+        const uint32_t lo = static_cast<uint32_t>(w) & 0xffffffu, hi = static_cast<uint32_t>(w >> 24);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            q[e] = static_cast<float>((lo >> (6 * e)) & 63u);
+            q[4 + e] = static_cast<float>((hi >> (6 * e)) & 63u);
         }
     } else {
 #pragma unroll
@@ -434,6 +441,11 @@ __device__ __forceinline__ void store_codes_at(uint8_t* p, uint64_t w) {
         *reinterpret_cast<uint32_t*>(p) = static_cast<uint32_t>(w);
     } else if constexpr (BITS == 2) {
         *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(w);
+    } else if constexpr (BITS == 6) {                // 6 bytes, 2-byte aligned
+        uint16_t* h = reinterpret_cast<uint16_t*>(p);
+        h[0] = static_cast<uint16_t>(w);
+        h[1] = static_cast<uint16_t>(w >> 16);
+        h[2] = static_cast<uint16_t>(w >> 32);
     } else {
         p[0] = static_cast<uint8_t>(w);
         p[1] = static_cast<uint8_t>(w >> 8);
@@ -450,6 +462,10 @@ __device__ __forceinline__ uint64_t load_codes_at(const uint8_t* p) {
         return *reinterpret_cast<const uint32_t*>(p);
     } else if constexpr (BITS == 2) {
         return *reinterpret_cast<const uint16_t*>(p);
+    } else if constexpr (BITS == 6) {
+        const uint16_t* h = reinterpret_cast<const uint16_t*>(p);
+        return static_cast<uint64_t>(h[0]) | (static_cast<uint64_t>(h[1]) << 16) |
+               (static_cast<uint64_t>(h[2]) << 32);
     } else {
         return static_cast<uint32_t>(p[0]) | (static_cast<uint32_t>(p[1]) << 8) |
                (static_cast<uint32_t>(p[2]) << 16);

@@ -47,6 +47,7 @@ hipError_t launch_quant_team_dt(int bits, int rounding, int shape, LaunchGeom g,
     case 2: return launch_qt_round<DT, 2>(rounding, shape, g, a, stream);
     case 3: return launch_qt_round<DT, 3>(rounding, shape, g, a, stream);
     case 4: return launch_qt_round<DT, 4>(rounding, shape, g, a, stream);
+    case 6: return launch_qt_round<DT, 6>(rounding, shape, g, a, stream);
     case 8: return launch_qt_round<DT, 8>(rounding, shape, g, a, stream);
     default: return hipErrorInvalidValue;
     }
@@ -70,6 +71,7 @@ hipError_t launch_dequant_flat_dt(int bits, int unroll, LaunchGeom g, const Dequ
     case 2: return launch_df_unroll<DT, 2>(unroll, g, a, stream);
     case 3: return launch_df_unroll<DT, 3>(unroll, g, a, stream);
     case 4: return launch_df_unroll<DT, 4>(unroll, g, a, stream);
+    case 6: return launch_df_unroll<DT, 6>(unroll, g, a, stream);
     case 8: return launch_df_unroll<DT, 8>(unroll, g, a, stream);
     default: return hipErrorInvalidValue;
     }

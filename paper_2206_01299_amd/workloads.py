@@ -105,9 +105,9 @@ def gpt2_2bit_stochastic() -> BoundaryConfig:
 
 def deberta_3bit() -> BoundaryConfig:
     return BoundaryConfig(
-        name="deberta_1p5b_fw3_bw8", n_samples=100_000, batch=32, seq=256,
+        name="deberta_1p5b_fw3_bw6", n_samples=100_000, batch=32, seq=256,
         hidden=1536, dtype="bf16", fwd_bits=3, fwd_group=64,
-        fwd_rounding=NEAREST, bwd_bits=8, bwd_group=64, bwd_rounding=NEAREST,
+        fwd_rounding=NEAREST, bwd_bits=6, bwd_group=64, bwd_rounding=NEAREST,
         law="student_t3", drift=0.05, epochs=2, seed=3)
 
 

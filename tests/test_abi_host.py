@@ -42,7 +42,7 @@ def test_message_sizes():
 
 
 BAD = [
-    (dict(bits=5), -2), (dict(bits=0), -2), (dict(bits=16), -2),
+    (dict(bits=5), -2), (dict(bits=0), -2), (dict(bits=16), -2), (dict(bits=7), -2),
     (dict(group=0), -3), (dict(group=-8), -3), (dict(group=48), -3),     # 48 does not divide 1600
     (dict(bits=3, group=4, n_per=1600), -3),                              # 12 bits: not whole bytes
     (dict(bits=2, group=2, n_per=1600), -3),

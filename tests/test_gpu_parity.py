@@ -41,7 +41,7 @@ def _release_device_memory():
 # any-shape fallback), group counts that leave ragged tails in every tiling.
 # ---------------------------------------------------------------------------
 GROUPS = [8, 24, 64, 128, 200, 256, 520, 1000, 1536, 1600, 2048, 4096, 8200, 16384, 32768]
-ODD_GROUPS = {2: [4, 12, 20], 3: [], 4: [2, 6, 100], 8: [1, 3, 7, 50]}     # not multiples of 8
+ODD_GROUPS = {2: [4, 12, 20], 3: [], 4: [2, 6, 100], 6: [4, 12, 100], 8: [1, 3, 7, 50]}     # not multiples of 8
 HUGE_GROUPS = [40000]                                                       # beyond a workgroup
 
 
@@ -60,7 +60,7 @@ def _sweep(H, dtype, bits, group, rounding, gps):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
 def test_sweep_group_sizes_nearest(H, dtype, bits):
     for group in GROUPS:
         gps = 37 if group <= 2048 else 5
@@ -69,7 +69,7 @@ def test_sweep_group_sizes_nearest(H, dtype, bits):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
-@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
 def test_sweep_group_sizes_stochastic(H, dtype, bits):
     for group in [8, 64, 128, 1600, 4096, 8200]:
         gps = 37 if group <= 2048 else 5
@@ -123,7 +123,7 @@ def test_unchanged_activation_sends_zero_scale(H, dtype):
     tweak = W.storage_to_f32(act_np, dtype)
     tweak[1, 128:192] += 0.25
     act_np = W.to_storage(tweak, dtype)
-    for bits in (2, 3, 4, 8):
+    for bits in (2, 3, 4, 6, 8):
         m = W.to_torch(m_np.copy(), dtype, d)
         desc = B.make_desc(batch=3, n_per=1024, n_samples=6, bits=bits, group=64, dtype=dtype)
         codes = torch.empty(B.codes_bytes(desc), dtype=torch.uint8, device=d)

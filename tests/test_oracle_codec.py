@@ -17,7 +17,7 @@ import pytest
 from paper_2206_01299_amd import workloads as W
 
 DTYPES = ["f32", "f16", "bf16"]
-BITS = [2, 3, 4, 8]
+BITS = [2, 3, 4, 6, 8]
 
 
 def _ulp_of(x32, dtype):

@@ -112,7 +112,7 @@ def test_uniform_is_uniform(oracle):
 
 
 # ------------------------------------------------------------- bit stream
-@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
 def test_pack_is_little_endian_bitstream(oracle, bits):
     """Element j sits at stream bits [j*b, j*b+b): the stream read as one
     little-endian integer is sum_j q_j << (j*b)."""
@@ -128,7 +128,7 @@ def test_pack_is_little_endian_bitstream(oracle, bits):
         assert np.array_equal(oracle.unpack(got, count, bits), q)
 
 
-@pytest.mark.parametrize("bits", [2, 3, 4, 8])
+@pytest.mark.parametrize("bits", [2, 3, 4, 6, 8])
 def test_pack_unpack_exhaustive_small(oracle, bits):
     """Every level in every position of one 8-element block round-trips."""
     for pos in range(8):

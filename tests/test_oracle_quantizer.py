@@ -11,7 +11,7 @@ import numpy as np
 import pytest
 
 GOLDEN = Path(__file__).parent / "golden"
-BITS = [2, 3, 4, 8]
+BITS = [2, 3, 4, 6, 8]
 
 
 def exact_position(d, bits):
