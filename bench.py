@@ -86,6 +86,9 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-legs", action="store_true")
     ap.add_argument("--cpu-calls", type=int, default=0, help="oracle sample size (0 = auto)")
+    ap.add_argument("--m-bits", type=int, choices=[0, 2, 8], default=0,
+                    help="keep the previous messages as z-bit levels (Appendix H.5) instead of the "
+                         "activation dtype; 0 = full precision (the headline configuration)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
                          "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
@@ -95,7 +98,7 @@ def parse_args():
 class Workload:
     """Device-resident state of the benchmarked boundary."""
 
-    def __init__(self, cfg, pool: int, seed: int = 1234):
+    def __init__(self, cfg, pool: int, seed: int = 1234, m_bits: int = 0):
         import torch
         from paper_2206_01299_amd import binding as B
         self.torch, self.B, self.cfg = torch, B, cfg
@@ -113,8 +116,17 @@ class Workload:
         self.bdesc = B.make_desc(batch=Bn, n_per=n_per, n_samples=cfg.n_samples, bits=cfg.bwd_bits,
                                  group=cfg.bwd_group, dtype=cfg.dtype, rounding=cfg.bwd_rounding)
 
-        self.m_send = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
-        self.m_recv = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
+        self.m_bits = m_bits
+        if m_bits:      # previous messages as z-bit levels + one scale per group (Appendix H.5)
+            row = B.lowbit_row_bytes(self.fdesc, m_bits)
+            gps = n_per // cfg.fwd_group
+            self.m_send = torch.zeros((cfg.n_samples, row), dtype=torch.uint8, device=d)
+            self.m_recv = torch.zeros((cfg.n_samples, row), dtype=torch.uint8, device=d)
+            self.ms_send = torch.zeros((cfg.n_samples, gps), dtype=torch.float32, device=d)
+            self.ms_recv = torch.zeros((cfg.n_samples, gps), dtype=torch.float32, device=d)
+        else:
+            self.m_send = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
+            self.m_recv = torch.zeros((cfg.n_samples, n_per), dtype=td, device=d)
 
         # outliers: a fraction of the hidden channels, or of the token rows, carries a larger scale
         chan = torch.ones((1, cfg.hidden), device=d)
@@ -178,13 +190,21 @@ class Workload:
     def encode(self, k):
         s = k % self.pool
         self.fdesc.rng_seed = 0x5EED0000 + 2 * k           # a fresh key per message
-        self.B.encode(self.fdesc, self.act[s], self.ids[k % self.calls], self.m_send,
-                      self.codes[s], self.scales[s])
+        if self.m_bits:
+            self.B.encode_lowbit(self.fdesc, self.m_bits, self.act[s], self.ids[k % self.calls],
+                                 self.m_send, self.ms_send, self.codes[s], self.scales[s])
+        else:
+            self.B.encode(self.fdesc, self.act[s], self.ids[k % self.calls], self.m_send,
+                          self.codes[s], self.scales[s])
 
     def decode(self, k):
         s = k % self.pool
-        self.B.decode(self.fdesc, self.codes[s], self.scales[s], self.ids[k % self.calls],
-                      self.m_recv, self.out[s])
+        if self.m_bits:
+            self.B.decode_lowbit(self.fdesc, self.m_bits, self.codes[s], self.scales[s],
+                                 self.ids[k % self.calls], self.m_recv, self.ms_recv, self.out[s])
+        else:
+            self.B.decode(self.fdesc, self.codes[s], self.scales[s], self.ids[k % self.calls],
+                          self.m_recv, self.out[s])
 
     def grad_quant(self, k):
         s = k % self.pool
@@ -234,9 +254,11 @@ class Workload:
         n, E = c.n, c.elem_bytes
         fb, bb = c.fwd_bits / 8.0, c.bwd_bits / 8.0
         fs, bs = 4.0 * n / c.fwd_group, 4.0 * n / c.bwd_group
+        M = self.m_bits / 8.0 if self.m_bits else E   # bytes per element of the stored m
+        ss = 2 * fs if self.m_bits else 0.0           # storage scales, read and written
         return {
-            "encode": n * (E + E + E + fb) + fs,          # act, m read, m write, codes + scales
-            "decode": n * (fb + E + E + E) + fs,          # codes, m read, m write, out + scales
+            "encode": n * (E + M + M + fb) + fs + ss,     # act, m read, m write, codes + scales
+            "decode": n * (fb + M + M + E) + fs + ss,     # codes, m read, m write, out + scales
             "grad_quant": n * (E + bb) + bs,
             "grad_dequant": n * (bb + E) + bs,
         }
@@ -387,7 +409,7 @@ def main():
     if args.pool <= 0:
         args.pool = max(4, -(-1_250_000_000 // (cfg.n * cfg.elem_bytes)))
     t_setup = time.perf_counter()
-    wl = Workload(cfg, args.pool)
+    wl = Workload(cfg, args.pool, m_bits=args.m_bits)
     wl.preseed_and_drift()
     t_setup = time.perf_counter() - t_setup
 
@@ -418,7 +440,7 @@ def main():
     if legs:
         dominant = max(wl.LEGS, key=lambda l: legs[l]["avg_us"])
         a_gbps = lb[dominant] / (legs[dominant]["avg_us"] * 1e-6) / 1e9
-        traffic = read_traffic() if args.config == "gpt2_4bit" else None
+        traffic = read_traffic() if args.config == "gpt2_4bit" and not args.m_bits else None
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(a_gbps, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
                     "algorithmic_bytes_per_launch": lb[dominant],
@@ -458,7 +480,8 @@ def main():
                    "name": cfg.name,
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
-                   "group": cfg.fwd_group, "pool_slots": args.pool, "launch": args.launch, "streams": args.streams,
+                   "group": cfg.fwd_group, "m_bits": args.m_bits or None, "pool_slots": args.pool, "launch": args.launch,
+                   "streams": args.streams,
                    "cold_buffers": True, "device": torch.cuda.get_device_name(0),
                    "setup_s": round(t_setup, 1)},
         "roofline": roofline, "cpu_baseline": base,

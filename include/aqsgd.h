@@ -144,6 +144,31 @@ int aqsgd_seed(const aqsgd_desc* desc, const void* act, const int64_t* sample_id
                void* m_buf, void* stream);
 
 /*
+ * Previous messages kept at low precision ("m z", Appendix H.5: z bits for the
+ * previous messages; the appendix reports z = 8 and z = 2).  m(xi) is stored as z-bit
+ * levels plus one binary32 scale per group, produced by the same Q with nearest
+ * rounding; the group is the descriptor's.  Both stages work from the stored value
+ * m^ = Q_z^-1(stored):
+ *     sender:    Delta m = Q_b(act - m^)  -> codes, scales;   v = m^ + Delta m;  store Q_z(v)
+ *     receiver:  v = m^ + Q_b^-1(codes, scales);  out = dtype(v);                store Q_z(v)
+ * All-zero storage decodes to m^ = 0, so a first visit is direct quantisation.  After
+ * matching calls the two stages' storage is bit-identical.
+ *   m_bits    2 or 8 (else AQSGD_ERR_BITS)
+ *   m_codes   i/o  uint8 [n_samples, aqsgd_lowbit_row_bytes()], level e of a row at bits
+ *                  [e*z, e*z+z) of the row's byte stream
+ *   m_scales  i/o  float [n_samples, n_per / group]
+ *   group must be a multiple of 8 and at most 16384 here (else AQSGD_ERR_GROUP).
+ * Everything else as in aqsgd_encode / aqsgd_decode.
+ */
+size_t aqsgd_lowbit_row_bytes(const aqsgd_desc* desc, int32_t m_bits);
+int aqsgd_encode_lowbit(const aqsgd_desc* desc, int32_t m_bits, const void* act,
+                        const int64_t* sample_ids, uint8_t* m_codes, float* m_scales,
+                        uint8_t* codes, float* scales, void* stream);
+int aqsgd_decode_lowbit(const aqsgd_desc* desc, int32_t m_bits, const uint8_t* codes,
+                        const float* scales, const int64_t* sample_ids, uint8_t* m_codes,
+                        float* m_scales, void* out, void* stream);
+
+/*
  * Debug helper: checks on the device that sample_ids are distinct and in range.
  * `flag` is one device int32 the caller has zeroed; the kernel sets bit 0 if an id
  * is out of range and bit 1 if two ids are equal.  O(batch^2) comparisons.

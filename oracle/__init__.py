@@ -73,6 +73,10 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_oracle_encode.argtypes = [i32, i32, i64, i32, u64, i64, i64, vp, vp, vp, vp, vp]
         L.aqsgd_oracle_seed.restype = i32
         L.aqsgd_oracle_seed.argtypes = [i32, i64, i64, vp, vp, vp]
+        L.aqsgd_oracle_encode_lowbit.restype = i32
+        L.aqsgd_oracle_encode_lowbit.argtypes = [i32, i32, i32, i64, i32, u64, i64, i64, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_oracle_decode_lowbit.restype = i32
+        L.aqsgd_oracle_decode_lowbit.argtypes = [i32, i32, i32, i64, i64, i64, vp, vp, vp, vp, vp, vp]
         L.aqsgd_oracle_decode.restype = i32
         L.aqsgd_oracle_decode.argtypes = [i32, i32, i64, i64, i64, vp, vp, vp, vp, vp]
         L.aqsgd_oracle_grad_quant.restype = i32
@@ -261,4 +265,57 @@ def grad_dequant(codes: np.ndarray, scales: np.ndarray, *, dtype: str, bits: int
     rc = lib().aqsgd_oracle_grad_dequant(dt, bits, group, 1, n, _ptr(codes), _ptr(scales), _ptr(out))
     if rc:
         raise ValueError(f"oracle grad_dequant rejected its arguments (rc={rc})")
+    return out
+
+
+# -- previous messages kept at low precision ("m z") --------------------------
+def lowbit_state(n_rows: int, n_per: int, m_bits: int, group: int):
+    """All-zero storage for ``n_rows`` samples: (m_codes uint8 [rows, n_per*z/8],
+    m_scales float32 [rows, n_per/group])."""
+    return (np.zeros((n_rows, n_per * m_bits // 8), dtype=np.uint8),
+            np.zeros((n_rows, n_per // group), dtype=np.float32))
+
+
+def _lowbit_shapes(ids, m_codes, m_scales, m_bits, group):
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    _check(m_codes, np.uint8, "m_codes"); _check(m_scales, np.float32, "m_scales")
+    n_rows = m_codes.shape[0]
+    n_per = m_codes.shape[1] * 8 // m_bits
+    assert m_scales.shape == (n_rows, n_per // group)
+    assert ids.size == 0 or (ids.min() >= 0 and ids.max() < n_rows), "sample id out of range"
+    assert len(np.unique(ids)) == ids.size, "duplicate sample ids in one call"
+    return ids, n_per
+
+
+def encode_lowbit(act: np.ndarray, ids: np.ndarray, m_codes: np.ndarray, m_scales: np.ndarray, *,
+                  dtype: str, bits: int, m_bits: int, group: int, rounding: int = NEAREST, seed: int = 0):
+    """Sender with z-bit storage of m.  Updates the storage in place; returns (codes, scales)."""
+    dt = DTYPE_CODE[dtype]
+    _check(act, _NP_OF[dt], "act")
+    ids, n_per = _lowbit_shapes(ids, m_codes, m_scales, m_bits, group)
+    n = ids.size * n_per
+    assert act.size == n
+    codes = np.zeros(codes_bytes(n, bits), dtype=np.uint8)
+    scales = np.zeros(n // group, dtype=np.float32)
+    rc = lib().aqsgd_oracle_encode_lowbit(dt, bits, m_bits, group, rounding, seed, ids.size, n_per,
+                                          _ptr(act), _ptr(ids), _ptr(m_codes), _ptr(m_scales),
+                                          _ptr(codes), _ptr(scales))
+    if rc:
+        raise ValueError(f"oracle encode_lowbit rejected its arguments (rc={rc})")
+    return codes, scales
+
+
+def decode_lowbit(codes: np.ndarray, scales: np.ndarray, ids: np.ndarray, m_codes: np.ndarray,
+                  m_scales: np.ndarray, *, dtype: str, bits: int, m_bits: int, group: int) -> np.ndarray:
+    """Receiver with z-bit storage of m.  Updates the storage in place; returns the activation."""
+    dt = DTYPE_CODE[dtype]
+    _check(codes, np.uint8, "codes"); _check(scales, np.float32, "scales")
+    ids, n_per = _lowbit_shapes(ids, m_codes, m_scales, m_bits, group)
+    n = ids.size * n_per
+    assert codes.size == codes_bytes(n, bits) and scales.size == n // group
+    out = np.zeros(n, dtype=_NP_OF[dt])
+    rc = lib().aqsgd_oracle_decode_lowbit(dt, bits, m_bits, group, ids.size, n_per, _ptr(codes),
+                                          _ptr(scales), _ptr(ids), _ptr(m_codes), _ptr(m_scales), _ptr(out))
+    if rc:
+        raise ValueError(f"oracle decode_lowbit rejected its arguments (rc={rc})")
     return out

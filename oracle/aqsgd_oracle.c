@@ -418,3 +418,118 @@ int aqsgd_oracle_grad_dequant(int dtype, int bits, int64_t group, int64_t batch,
     }
     return 0;
 }
+
+/* ------------------------------------------------------------------ */
+/* Previous messages kept at low precision ("m z", Appendix H.5: "we    */
+/* perform quantization on m, where mz means that we use z bits for     */
+/* previous messages").  The appendix says no more than that; reading:  */
+/*   - m(xi) is stored as z-bit levels plus one binary32 max-abs scale   */
+/*     per group (the message's group size), through the same Q with     */
+/*     nearest rounding, so that both machines store the same bits;      */
+/*   - both machines work from the stored value m^ = Q_z^-1(stored):     */
+/*         sender:    Delta m = Q_b(a - m^)                              */
+/*         both:      v = m^ + Delta m   (binary32);  store Q_z(v)       */
+/*         receiver:  hands v (rounded to the activation dtype) on.      */
+/*   All-zero storage decodes to m^ = 0: the first visit is direct       */
+/*   quantisation, as with a full-precision m.                           */
+/* ------------------------------------------------------------------ */
+static int check_mbits(int m_bits, int64_t group)
+{
+    if (!(m_bits == 2 || m_bits == 8)) return -6;
+    if ((group * m_bits) % 8) return -3;
+    return 0;
+}
+
+/* m^ of one group from its stored levels and scale. */
+static void stored_group(const uint8_t* m_codes, float m_scale, int64_t group, int m_bits,
+                         int32_t* q, float* m_hat)
+{
+    aqsgd_oracle_unpack(m_codes, group, m_bits, q);
+    aqsgd_oracle_dequantize_group(q, m_scale, group, m_bits, m_hat);
+}
+
+/* Q_z(v), nearest, written back as levels and scale. */
+static void store_group(const float* v, int64_t group, int m_bits, float* half, int32_t* q,
+                        float* scratch, uint8_t* m_codes, float* m_scale)
+{
+    for (int64_t e = 0; e < group; ++e) half[e] = 0.5f;
+    aqsgd_oracle_quantize_group(v, half, group, m_bits, q, m_scale, scratch);
+    aqsgd_oracle_pack(q, group, m_bits, m_codes);
+}
+
+int aqsgd_oracle_encode_lowbit(int dtype, int bits, int m_bits, int64_t group, int rounding,
+                               uint64_t seed, int64_t batch, int64_t n_per, const void* act,
+                               const int64_t* ids, uint8_t* m_codes, float* m_scales,
+                               uint8_t* codes, float* scales)
+{
+    int rc = check_shape(dtype, bits, group, rounding, batch, n_per);
+    if (!rc) rc = check_mbits(m_bits, group);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    const int64_t n_groups = batch * groups_per_sample;
+#pragma omp parallel
+    {
+        float* m_hat = malloc(sizeof(float) * group);
+        float* d = malloc(sizeof(float) * group);
+        float* r = malloc(sizeof(float) * group);
+        float* dhat = malloc(sizeof(float) * group);
+        float* v = malloc(sizeof(float) * group);
+        float* tmp = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t i = g / groups_per_sample;
+            const int64_t gs = g % groups_per_sample;
+            const int64_t a0 = i * n_per + gs * group;                    /* = g * group */
+            uint8_t* mc = m_codes + (ids[i] * n_per + gs * group) * m_bits / 8;
+            float* ms = m_scales + ids[i] * groups_per_sample + gs;
+            stored_group(mc, *ms, group, m_bits, q, m_hat);
+            for (int64_t e = 0; e < group; ++e) d[e] = load_elem(act, a0 + e, dtype) - m_hat[e];
+            rounding_offsets(rounding, seed, a0, group, r);
+            aqsgd_oracle_quantize_group(d, r, group, bits, q, &scales[g], dhat);
+            aqsgd_oracle_pack(q, group, bits, codes + a0 * bits / 8);
+            for (int64_t e = 0; e < group; ++e) v[e] = m_hat[e] + dhat[e];
+            store_group(v, group, m_bits, r, q, tmp, mc, ms);
+        }
+        free(m_hat); free(d); free(r); free(dhat); free(v); free(tmp); free(q);
+    }
+    return 0;
+}
+
+int aqsgd_oracle_decode_lowbit(int dtype, int bits, int m_bits, int64_t group, int64_t batch,
+                               int64_t n_per, const uint8_t* codes, const float* scales,
+                               const int64_t* ids, uint8_t* m_codes, float* m_scales, void* out)
+{
+    int rc = check_shape(dtype, bits, group, ORACLE_NEAREST, batch, n_per);
+    if (!rc) rc = check_mbits(m_bits, group);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    const int64_t n_groups = batch * groups_per_sample;
+#pragma omp parallel
+    {
+        float* m_hat = malloc(sizeof(float) * group);
+        float* dhat = malloc(sizeof(float) * group);
+        float* v = malloc(sizeof(float) * group);
+        float* half = malloc(sizeof(float) * group);
+        float* tmp = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t i = g / groups_per_sample;
+            const int64_t gs = g % groups_per_sample;
+            const int64_t a0 = i * n_per + gs * group;
+            uint8_t* mc = m_codes + (ids[i] * n_per + gs * group) * m_bits / 8;
+            float* ms = m_scales + ids[i] * groups_per_sample + gs;
+            stored_group(mc, *ms, group, m_bits, q, m_hat);
+            aqsgd_oracle_unpack(codes + a0 * bits / 8, group, bits, q);
+            aqsgd_oracle_dequantize_group(q, scales[g], group, bits, dhat);
+            for (int64_t e = 0; e < group; ++e) {
+                v[e] = m_hat[e] + dhat[e];
+                store_elem(out, a0 + e, dtype, v[e]);
+            }
+            store_group(v, group, m_bits, half, q, tmp, mc, ms);
+        }
+        free(m_hat); free(dhat); free(v); free(half); free(tmp); free(q);
+    }
+    return 0;
+}

@@ -22,7 +22,8 @@ DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
-           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_check_ids",
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_lowbit_row_bytes",
+           "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_check_ids",
            "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
@@ -66,6 +67,12 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_grad_dequant.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_seed.restype = ctypes.c_int
         L.aqsgd_seed.argtypes = [dp, vp, vp, vp, vp]
+        L.aqsgd_lowbit_row_bytes.restype = ctypes.c_size_t
+        L.aqsgd_lowbit_row_bytes.argtypes = [dp, ctypes.c_int32]
+        L.aqsgd_encode_lowbit.restype = ctypes.c_int
+        L.aqsgd_encode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_decode_lowbit.restype = ctypes.c_int
+        L.aqsgd_decode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.aqsgd_check_ids.restype = ctypes.c_int
         L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
         L.aqsgd_profile_next_launch.restype = ctypes.c_int
@@ -144,6 +151,28 @@ def seed(desc: Desc, act, sample_ids, m_buf, stream=None) -> None:
     """``aqsgd_seed``: uncompressed first visit, ``m_buf[sample_ids] <- act``."""
     _raise(lib().aqsgd_seed(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
                             _dev(m_buf, "m_buf"), _stream(stream)))
+
+
+def lowbit_row_bytes(desc: Desc, m_bits: int) -> int:
+    return int(lib().aqsgd_lowbit_row_bytes(ctypes.byref(desc), m_bits))
+
+
+def encode_lowbit(desc: Desc, m_bits: int, act, sample_ids, m_codes, m_scales, codes, scales,
+                  stream=None) -> None:
+    """``aqsgd_encode_lowbit``: sender with z-bit storage of the previous messages."""
+    _raise(lib().aqsgd_encode_lowbit(ctypes.byref(desc), m_bits, _dev(act, "act"),
+                                     _dev(sample_ids, "sample_ids"), _dev(m_codes, "m_codes"),
+                                     _dev(m_scales, "m_scales"), _dev(codes, "codes"),
+                                     _dev(scales, "scales"), _stream(stream)))
+
+
+def decode_lowbit(desc: Desc, m_bits: int, codes, scales, sample_ids, m_codes, m_scales, out,
+                  stream=None) -> None:
+    """``aqsgd_decode_lowbit``: receiver with z-bit storage of the previous messages."""
+    _raise(lib().aqsgd_decode_lowbit(ctypes.byref(desc), m_bits, _dev(codes, "codes"),
+                                     _dev(scales, "scales"), _dev(sample_ids, "sample_ids"),
+                                     _dev(m_codes, "m_codes"), _dev(m_scales, "m_scales"),
+                                     _dev(out, "out"), _stream(stream)))
 
 
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:

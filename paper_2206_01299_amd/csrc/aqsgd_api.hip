@@ -4,6 +4,7 @@
 #include <limits>
 
 #include "aqsgd_kernels.h"
+#include "aqsgd_lowbit.h"
 
 namespace aqsgd {
 
@@ -43,6 +44,16 @@ hipError_t launch_dequant_anyshape(int dtype, int bits, LaunchGeom g, const Dequ
     case AQSGD_F32:  return launch_dequant_anyshape_dt<AQSGD_F32>(bits, g, a, s);
     case AQSGD_F16:  return launch_dequant_anyshape_dt<AQSGD_F16>(bits, g, a, s);
     case AQSGD_BF16: return launch_dequant_anyshape_dt<AQSGD_BF16>(bits, g, a, s);
+    default:         return hipErrorInvalidValue;
+    }
+}
+
+hipError_t launch_lowbit(int dtype, int bits, int m_bits, int shape, bool sender, LaunchGeom g,
+                         const LowbitArgs& a, hipStream_t s) {
+    switch (dtype) {
+    case AQSGD_F32:  return launch_lowbit_dt<AQSGD_F32>(bits, m_bits, shape, sender, g, a, s);
+    case AQSGD_F16:  return launch_lowbit_dt<AQSGD_F16>(bits, m_bits, shape, sender, g, a, s);
+    case AQSGD_BF16: return launch_lowbit_dt<AQSGD_BF16>(bits, m_bits, shape, sender, g, a, s);
     default:         return hipErrorInvalidValue;
     }
 }
@@ -197,6 +208,51 @@ void seed_rows_elem_kernel(const T* act, const int64_t* ids, T* m_buf, int64_t n
     }
 }
 
+int lowbit_shape_for(int cpg) {
+    if (cpg <= 8) return kLb8x1;
+    if (cpg <= 16) return kLb16x1;
+    if (cpg <= 32) return kLb32x1;
+    if (cpg <= 64) return kLb64x1;
+    if (cpg <= 128) return kLb64x2;
+    if (cpg <= 256) return kLb64x4;
+    if (cpg <= 512) return kLb256x2;
+    if (cpg <= 1024) return kLb256x4;
+    return kLb1024x2;
+}
+
+int lowbit_teams_per_block(int shape) {
+    switch (shape) {
+    case kLb8x1: return kBlock / 8;
+    case kLb16x1: return kBlock / 16;
+    case kLb32x1: return kBlock / 32;
+    case kLb64x1: case kLb64x2: case kLb64x4: return kBlock / 64;
+    default: return 1;
+    }
+}
+
+int check_lowbit(const aqsgd_desc* d, int32_t m_bits) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (m_bits != 2 && m_bits != 8) return AQSGD_ERR_BITS;
+    if (d->group % kChunk != 0 || d->group / kChunk > kMaxLowbitChunks) return AQSGD_ERR_GROUP;
+    return AQSGD_OK;
+}
+
+int run_lowbit(const aqsgd_desc* d, int32_t m_bits, bool sender, const void* act, void* out,
+               const int64_t* ids, uint8_t* m_codes, float* m_scales, uint8_t* codes, float* scales,
+               hipStream_t stream) {
+    LowbitArgs a;
+    a.act = act; a.out = out; a.ids = ids; a.m_codes = m_codes; a.m_scales = m_scales;
+    a.codes = codes; a.scales = scales;
+    a.n_per = d->n_per; a.gps = d->n_per / d->group;
+    a.batch = static_cast<int32_t>(d->batch); a.group = d->group; a.cpg = d->group / kChunk;
+    a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
+    const int shape = lowbit_shape_for(a.cpg);
+    const hipError_t err = launch_lowbit(d->dtype, d->bits, m_bits, shape, sender,
+                                         geometry(a.gps, lowbit_teams_per_block(shape), d->batch), a, stream);
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
 __global__ void check_ids_kernel(const int64_t* ids, int64_t batch, int64_t n_samples, int32_t* flag) {
     int bad = 0;
     for (int64_t i = threadIdx.x + static_cast<int64_t>(blockIdx.x) * blockDim.x; i < batch;
@@ -308,6 +364,38 @@ int aqsgd_seed(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, 
                                 d->n_per, static_cast<int>(d->batch));
     }
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+size_t aqsgd_lowbit_row_bytes(const aqsgd_desc* d, int32_t m_bits) {
+    if (check_lowbit(d, m_bits) != AQSGD_OK) return 0;
+    return static_cast<size_t>(d->n_per) * m_bits / 8;
+}
+
+int aqsgd_encode_lowbit(const aqsgd_desc* d, int32_t m_bits, const void* act, const int64_t* sample_ids,
+                        uint8_t* m_codes, float* m_scales, uint8_t* codes, float* scales, void* stream) {
+    const int rc = check_lowbit(d, m_bits);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!act || !sample_ids || !m_codes || !m_scales || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(m_codes, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(m_scales, 4) || !aligned(sample_ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return run_lowbit(d, m_bits, true, act, nullptr, sample_ids, m_codes, m_scales, codes, scales,
+                      static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_decode_lowbit(const aqsgd_desc* d, int32_t m_bits, const uint8_t* codes, const float* scales,
+                        const int64_t* sample_ids, uint8_t* m_codes, float* m_scales, void* out,
+                        void* stream) {
+    const int rc = check_lowbit(d, m_bits);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!codes || !scales || !sample_ids || !m_codes || !m_scales || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(m_codes, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(m_scales, 4) || !aligned(sample_ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return run_lowbit(d, m_bits, false, nullptr, out, sample_ids, m_codes, m_scales,
+                      const_cast<uint8_t*>(codes), const_cast<float*>(scales), static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples, int32_t* flag,

@@ -1,0 +1,252 @@
+// Codec kernels for previous messages kept at low precision ("m z", Appendix
+// H.5 of the paper): m(xi) lives in HBM as z-bit levels plus one binary32 scale
+// per group instead of the activation dtype, which cuts both the footprint and
+// the dominant traffic of the boundary (config 2 at z = 8: 4.5 instead of 6.5
+// bytes per element and call).
+//
+// Both machines work from the stored value m^ = Q_z^-1(stored):
+//     sender:    Delta m = Q_b(a - m^)           -> codes, scales on the wire
+//     both:      v = m^ + Delta m  (binary32);   store Q_z(v), nearest rounding
+//     receiver:  out = dtype(v)
+// One team of lanes owns a group, as in quant_team_kernel, and runs two max
+// reductions: over |a - m^| for the wire scale and over |v| for the storage
+// scale.  Everything between the loads and the stores stays in registers.
+#pragma once
+
+#include "aqsgd_kernels.h"
+
+namespace aqsgd {
+
+struct LowbitArgs {
+    const void* act;           // sender: [batch, n_per]; receiver: unused
+    void* out;                 // receiver: [batch, n_per]; sender: unused
+    const int64_t* ids;
+    uint8_t* m_codes;          // [n_samples, n_per * MBITS / 8]
+    float* m_scales;           // [n_samples, gps]
+    uint8_t* codes;            // the message: written by the sender, read by the receiver
+    float* scales;
+    int64_t n_per;
+    int64_t gps;
+    int32_t batch;
+    int32_t group;
+    int32_t cpg;
+    int32_t stochastic;        // sender: rounding mode of the message
+    uint64_t seed;
+};
+
+template <int TEAM, int KIND>
+__device__ __forceinline__ float team_max_all(float mx, float* wave_max) {
+    constexpr bool kMultiWave = TEAM > kWave;
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
+    mx = team_max<(TEAM < kWave ? TEAM : kWave)>(mx);
+    if constexpr (kMultiWave) {
+        float* slot = wave_max + KIND * (kThreads / kWave);      // one array per reduction
+        __syncthreads();
+        if (threadIdx.x % kWave == 0) slot[threadIdx.x / kWave] = mx;
+        __syncthreads();
+#pragma unroll
+        for (int w = 0; w < kThreads / kWave; ++w) mx = __builtin_fmaxf(mx, slot[w]);
+    }
+    return mx;
+}
+
+template <int DT, int BITS, int MBITS, int TEAM, int CPL, bool SENDER>
+__device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const char* act_s, char* out_s,
+                                                  uint8_t* mcodes_s, float* mscales_s, uint8_t* codes_s,
+                                                  float* scales_s, int64_t src0, int64_t g,
+                                                  const uint32_t (&cc)[CPL], int lane_in_team,
+                                                  float* wave_max) {
+    constexpr int kEB = ElemBytes<DT>::value;
+    constexpr int kChunkBytes = kChunk * kEB;
+    const int64_t goff = g * a.group;                    // element offset within the sample
+    const int64_t gchunk = goff / kChunk;
+
+    // ---- issue every load of the group ------------------------------------------
+    uint64_t mw[CPL], cw[CPL];
+    Raw<DT> ra[CPL];
+    const float m_scale = mscales_s[g];
+    float wire_scale = 0.0f;
+    if constexpr (!SENDER) wire_scale = scales_s[g];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        mw[k] = load_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS);
+        if constexpr (SENDER) ra[k] = load_raw_at<DT>(act_s + goff * kEB + cc[k] * kChunkBytes);
+        else cw[k] = load_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- m^ = Q_z^-1(stored) ---------------------------------------------------------
+    const GroupScale msc = scale_from_wire<MBITS>(m_scale);
+    float v[CPL][kChunk];                                // holds m^, then v = m^ + Delta m
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        float q[kChunk];
+        unpack_levels<MBITS>(mw[k], q);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) v[k][e] = value_of(q[e], msc);
+    }
+
+    if constexpr (SENDER) {
+        // ---- Delta m = Q_b(a - m^) ------------------------------------------------------
+        float d[CPL][kChunk];
+        float mx = 0.0f;
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            float av[kChunk];
+            unpack_raw<DT>(ra[k], av);
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) {
+                d[k][e] = av[e] - v[k][e];
+                mx = __builtin_fmaxf(mx, __builtin_fabsf(d[k][e]));
+            }
+        }
+        mx = team_max_all<TEAM, 0>(mx, wave_max);
+        const GroupScale sc = make_scale<BITS>(mx);
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            float r[kChunk];
+            if (a.stochastic) {
+                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
+            } else {
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
+            }
+            float q[kChunk];
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) {
+                // the upper clamp of the stochastic form is a no-op for r = 1/2
+                q[e] = level_of<BITS, AQSGD_ROUND_STOCHASTIC>(d[k][e], sc, r[e]);
+                v[k][e] = v[k][e] + value_of(q[e], sc);
+            }
+            store_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS, pack_levels<BITS>(q));
+        }
+        if (lane_in_team == 0) scales_s[g] = sc.s_tx;
+    } else {
+        const GroupScale wsc = scale_from_wire<BITS>(wire_scale);
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            float q[kChunk];
+            unpack_levels<BITS>(cw[k], q);
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) v[k][e] = v[k][e] + value_of(q[e], wsc);
+        }
+    }
+
+    // ---- store Q_z(v); the receiver also hands v on ------------------------------------
+    float mx2 = 0.0f;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
+    mx2 = team_max_all<TEAM, 1>(mx2, wave_max);
+    const GroupScale ssc = make_scale<MBITS>(mx2);
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        float q[kChunk];
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) q[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, 0.5f);
+        store_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS, pack_levels<MBITS>(q));
+        if constexpr (!SENDER) store_raw_at<DT>(out_s + goff * kEB + cc[k] * kChunkBytes, pack_raw<DT>(v[k]));
+    }
+    if (lane_in_team == 0) mscales_s[g] = ssc.s_tx;
+}
+
+template <int DT, int BITS, int MBITS, int TEAM, int CPL, bool SENDER>
+__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
+void lowbit_team_kernel(const LowbitArgs a) {
+    constexpr bool kMultiWave = TEAM > kWave;
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
+    constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
+    constexpr int kEB = ElemBytes<DT>::value;
+    [[maybe_unused]] __shared__ float wave_max[2 * (kThreads / kWave)];
+
+    const int lane_in_team = threadIdx.x % TEAM;
+    const int team = kMultiWave ? 0
+                     : (TEAM == kWave ? __builtin_amdgcn_readfirstlane(threadIdx.x / kWave)
+                                      : static_cast<int>(threadIdx.x / TEAM));
+    uint32_t cc[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+        cc[k] = static_cast<uint32_t>(min(k * TEAM + lane_in_team, a.cpg - 1));
+
+    for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
+        const int64_t row = a.ids[i];
+        const int64_t src0 = static_cast<int64_t>(i) * a.n_per;
+        const char* act_s = SENDER ? static_cast<const char*>(a.act) + src0 * kEB : nullptr;
+        char* out_s = SENDER ? nullptr : static_cast<char*>(a.out) + src0 * kEB;
+        uint8_t* mcodes_s = a.m_codes + row * (a.n_per / kChunk * MBITS);
+        float* mscales_s = a.m_scales + row * a.gps;
+        uint8_t* codes_s = a.codes + src0 / kChunk * BITS;
+        float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
+
+        for (int64_t gbase = static_cast<int64_t>(blockIdx.x) * kTeamsPerBlock; gbase < a.gps;
+             gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
+            const int64_t g = gbase + team;
+            if (g < a.gps)
+                lowbit_team_group<DT, BITS, MBITS, TEAM, CPL, SENDER>(a, act_s, out_s, mcodes_s, mscales_s,
+                                                                      codes_s, scales_s, src0, g, cc,
+                                                                      lane_in_team, wave_max);
+        }
+    }
+}
+
+// Team shapes of the low-precision-storage kernels (more live registers per
+// element than the plain codec, so the widest shapes stop at two chunks per lane).
+enum LowbitShape {
+    kLb8x1 = 0, kLb16x1, kLb32x1, kLb64x1, kLb64x2, kLb64x4, kLb256x2, kLb256x4, kLb1024x2, kNumLowbitShapes
+};
+constexpr int kMaxLowbitChunks = 2048;
+
+hipError_t launch_lowbit(int dtype, int bits, int m_bits, int shape, bool sender, LaunchGeom g,
+                         const LowbitArgs& a, hipStream_t stream);
+template <int DT> hipError_t launch_lowbit_dt(int bits, int m_bits, int shape, bool sender, LaunchGeom g,
+                                              const LowbitArgs& a, hipStream_t stream);
+
+// ---- launch table (instantiated per dtype in aqsgd_lowbit_<dtype>.hip) ----------------
+template <int DT, int BITS, int MBITS, bool SENDER>
+static hipError_t launch_lb_shape(int shape, LaunchGeom g, const LowbitArgs& a, hipStream_t s) {
+    const dim3 grid(g.grid_x, g.grid_y);
+    switch (shape) {
+    case kLb8x1:    return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 8, 1, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb16x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 16, 1, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb32x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 32, 1, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb64x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 1, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb64x2:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb64x4:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, SENDER>, grid, dim3(kBlock), s, a);
+    case kLb256x2:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 2, SENDER>, grid, dim3(256), s, a);
+    case kLb256x4:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 4, SENDER>, grid, dim3(256), s, a);
+    case kLb1024x2: return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 1024, 2, SENDER>, grid, dim3(1024), s, a);
+    default:        return hipErrorInvalidValue;
+    }
+}
+
+template <int DT, int BITS>
+static hipError_t launch_lb_mbits(int m_bits, int shape, bool sender, LaunchGeom g, const LowbitArgs& a,
+                                  hipStream_t s) {
+    if (m_bits == 8)
+        return sender ? launch_lb_shape<DT, BITS, 8, true>(shape, g, a, s)
+                      : launch_lb_shape<DT, BITS, 8, false>(shape, g, a, s);
+    if (m_bits == 2)
+        return sender ? launch_lb_shape<DT, BITS, 2, true>(shape, g, a, s)
+                      : launch_lb_shape<DT, BITS, 2, false>(shape, g, a, s);
+    return hipErrorInvalidValue;
+}
+
+template <int DT>
+hipError_t launch_lowbit_dt(int bits, int m_bits, int shape, bool sender, LaunchGeom g, const LowbitArgs& a,
+                            hipStream_t s) {
+    switch (bits) {
+    case 2: return launch_lb_mbits<DT, 2>(m_bits, shape, sender, g, a, s);
+    case 3: return launch_lb_mbits<DT, 3>(m_bits, shape, sender, g, a, s);
+    case 4: return launch_lb_mbits<DT, 4>(m_bits, shape, sender, g, a, s);
+    case 6: return launch_lb_mbits<DT, 6>(m_bits, shape, sender, g, a, s);
+    case 8: return launch_lb_mbits<DT, 8>(m_bits, shape, sender, g, a, s);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+#define AQSGD_INSTANTIATE_LOWBIT_DTYPE(DT)                                                        \
+    template hipError_t launch_lowbit_dt<DT>(int, int, int, bool, LaunchGeom, const LowbitArgs&,  \
+                                             hipStream_t);
+
+}  // namespace aqsgd

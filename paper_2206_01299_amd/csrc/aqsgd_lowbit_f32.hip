@@ -1,0 +1,6 @@
+// Low-precision-storage codec kernels instantiated for f32 activations and outputs.
+#include "aqsgd_lowbit.h"
+
+namespace aqsgd {
+AQSGD_INSTANTIATE_LOWBIT_DTYPE(AQSGD_F32)
+}
