@@ -42,7 +42,9 @@
  * stream against Python big-integer arithmetic; the level decision against
  * exact rational arithmetic; the hand-worked two-visit example; the paper's
  * invariants (first visit = direct quantisation, replica identity, error
- * bound, unbiasedness, contraction, message size).  No function here is
+ * bound, unbiasedness, contraction, message size); the uncompressed first
+ * visit and the low-precision storage of m (end of this file) against their
+ * own invariants and the appendix's ordering of errors.  No function here is
  * "parity unpinned".
  */
 #include <math.h>
