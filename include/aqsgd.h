@@ -169,6 +169,43 @@ int aqsgd_decode_lowbit(const aqsgd_desc* desc, int32_t m_bits, const uint8_t* c
                         float* m_scales, void* out, void* stream);
 
 /*
+ * Host-memory tier for the previous messages (Section 3.3, "System Implementations
+ * and Optimizations": m(xi) is kept in a local buffer in host memory, loaded to the
+ * GPU before the forward pass of its sample and written back after the update, both
+ * hidden behind the computation of other samples; Appendix G).
+ *
+ * All N rows live in PINNED HOST memory; HBM holds `slots` windows of `batch` rows.
+ * A micro-batch's rows are copied into a window ahead of time on a copy stream
+ * (prefetch), the codec runs on the window with the window's row numbers as its
+ * sample ids (acquire), and the updated rows go back afterwards (release).  Memory is
+ * the caller's: host_rows [n_samples, row_bytes] pinned (hipHostMalloc / a pinned
+ * tensor), dev_rows [slots*batch, row_bytes] and dev_row_ids int64 [slots*batch] on the
+ * device.  The tier object only holds the events that order the two streams, plus
+ * which samples each window holds.  Calls on one tier must come from one host thread.
+ *
+ *   create    fills dev_row_ids with 0 .. slots*batch-1 (synchronously) and creates events
+ *   prefetch  window <- host rows of host_ids (HOST int64[batch], distinct), on copy_stream;
+ *             a window must be released before it is prefetched again
+ *   acquire   makes compute_stream wait for the window's rows; returns the sample_ids
+ *             pointer (device, batch entries) to pass to the codec with m_buf = dev_rows,
+ *             n_samples = slots*batch
+ *   release   after the codec calls queued so far on compute_stream, copies the window's
+ *             rows back to their host rows on copy_stream
+ *   drain     blocks until every copy issued so far has finished (host rows are current)
+ * Return: AQSGD_OK, AQSGD_ERR_NULL / _SHAPE for bad arguments, AQSGD_ERR_LAUNCH if the
+ * HIP runtime fails.
+ */
+typedef struct aqsgd_tier aqsgd_tier;
+int aqsgd_tier_create(aqsgd_tier** tier, void* host_rows, void* dev_rows, int64_t* dev_row_ids,
+                      int64_t n_samples, int64_t row_bytes, int32_t slots, int32_t batch);
+int aqsgd_tier_prefetch(aqsgd_tier* tier, int32_t slot, const int64_t* host_ids, void* copy_stream);
+int aqsgd_tier_acquire(aqsgd_tier* tier, int32_t slot, void* compute_stream,
+                       const int64_t** sample_ids);
+int aqsgd_tier_release(aqsgd_tier* tier, int32_t slot, void* compute_stream, void* copy_stream);
+int aqsgd_tier_drain(aqsgd_tier* tier);
+void aqsgd_tier_destroy(aqsgd_tier* tier);
+
+/*
  * Debug helper: checks on the device that sample_ids are distinct and in range.
  * `flag` is one device int32 the caller has zeroed; the kernel sets bit 0 if an id
  * is out of range and bit 1 if two ids are equal.  O(batch^2) comparisons.

@@ -23,7 +23,9 @@ DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
            "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_lowbit_row_bytes",
-           "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_check_ids",
+           "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
+           "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
+           "aqsgd_check_ids",
            "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
@@ -73,6 +75,19 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_encode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.aqsgd_decode_lowbit.restype = ctypes.c_int
         L.aqsgd_decode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_tier_create.restype = ctypes.c_int
+        L.aqsgd_tier_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
+                                        ctypes.c_int32, ctypes.c_int32]
+        L.aqsgd_tier_prefetch.restype = ctypes.c_int
+        L.aqsgd_tier_prefetch.argtypes = [vp, ctypes.c_int32, vp, vp]
+        L.aqsgd_tier_acquire.restype = ctypes.c_int
+        L.aqsgd_tier_acquire.argtypes = [vp, ctypes.c_int32, vp, ctypes.POINTER(vp)]
+        L.aqsgd_tier_release.restype = ctypes.c_int
+        L.aqsgd_tier_release.argtypes = [vp, ctypes.c_int32, vp, vp]
+        L.aqsgd_tier_drain.restype = ctypes.c_int
+        L.aqsgd_tier_drain.argtypes = [vp]
+        L.aqsgd_tier_destroy.restype = None
+        L.aqsgd_tier_destroy.argtypes = [vp]
         L.aqsgd_check_ids.restype = ctypes.c_int
         L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
         L.aqsgd_profile_next_launch.restype = ctypes.c_int
@@ -186,3 +201,55 @@ def profile_next_launch(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> 
     (a torch event is created by its first ``record()``)."""
     _raise(lib().aqsgd_profile_next_launch(ctypes.c_void_p(start.cuda_event),
                                            ctypes.c_void_p(stop.cuda_event)))
+
+
+class Tier:
+    """Handle of ``aqsgd_tier``: previous messages in pinned host memory, ``slots``
+    windows of ``batch`` rows in HBM.  The three tensors are the caller's memory
+    (``host_rows`` pinned [N, row], ``dev_rows`` [slots*batch, row], ``dev_row_ids``
+    int64 [slots*batch]); this object only forwards calls and keeps them alive."""
+
+    def __init__(self, host_rows, dev_rows, dev_row_ids, slots: int, batch: int):
+        if not host_rows.is_pinned() or host_rows.is_cuda or not host_rows.is_contiguous():
+            raise ValueError("host_rows must be a contiguous pinned host tensor")
+        if dev_rows.shape[0] != slots * batch or dev_row_ids.numel() != slots * batch:
+            raise ValueError("dev_rows / dev_row_ids must hold slots * batch rows")
+        self.host_rows, self.dev_rows, self.dev_row_ids = host_rows, dev_rows, dev_row_ids
+        self.slots, self.batch = slots, batch
+        row_bytes = host_rows[0].numel() * host_rows.element_size()
+        self._h = ctypes.c_void_p()
+        _raise(lib().aqsgd_tier_create(ctypes.byref(self._h), ctypes.c_void_p(host_rows.data_ptr()),
+                                       _dev(dev_rows, "dev_rows"), _dev(dev_row_ids, "dev_row_ids"),
+                                       host_rows.shape[0], row_bytes, slots, batch))
+
+    def prefetch(self, slot: int, host_ids, copy_stream) -> None:
+        """``host_ids``: host int64 tensor of ``batch`` distinct sample ids."""
+        if host_ids.is_cuda or host_ids.dtype != torch.int64 or host_ids.numel() != self.batch:
+            raise ValueError("host_ids must be a host int64 tensor with one id per row of the window")
+        _raise(lib().aqsgd_tier_prefetch(self._h, slot, ctypes.c_void_p(host_ids.data_ptr()),
+                                         _stream(copy_stream)))
+
+    def acquire(self, slot: int, compute_stream=None):
+        """Returns the window's sample ids (a view of ``dev_row_ids``) for the codec call."""
+        p = ctypes.c_void_p()
+        _raise(lib().aqsgd_tier_acquire(self._h, slot, _stream(compute_stream), ctypes.byref(p)))
+        ids = self.dev_row_ids[slot * self.batch:(slot + 1) * self.batch]
+        assert ids.data_ptr() == p.value
+        return ids
+
+    def release(self, slot: int, compute_stream, copy_stream) -> None:
+        _raise(lib().aqsgd_tier_release(self._h, slot, _stream(compute_stream), _stream(copy_stream)))
+
+    def drain(self) -> None:
+        _raise(lib().aqsgd_tier_drain(self._h))
+
+    def close(self) -> None:
+        if self._h:
+            lib().aqsgd_tier_destroy(self._h)
+            self._h = ctypes.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

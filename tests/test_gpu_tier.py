@@ -1,0 +1,133 @@
+"""GPU test of the host-memory tier for the previous messages (Section 3.3 of the
+paper: m(xi) in host memory, prefetched before its sample's forward pass and
+written back after the update).  The codec must produce the same bytes whether
+m lives in one big HBM array or is paged through a few HBM windows."""
+import time
+
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2206_01299_amd import binding as B
+from paper_2206_01299_amd import workloads as W
+
+
+@pytest.fixture(scope="module")
+def H():
+    if not torch.cuda.is_available():
+        pytest.fail("these tests need the MI355X; run them with -m gpu on the GPU box")
+    B.lib()
+    import oracle
+    oracle.build()
+    import gpu_harness
+    return gpu_harness
+
+
+def _tier(cfg, slots, d):
+    td = B.DTYPE_NAME[cfg.dtype]
+    host = torch.zeros((cfg.n_samples, cfg.n_per), dtype=td).pin_memory()
+    dev = torch.zeros((slots * cfg.batch, cfg.n_per), dtype=td, device=d)
+    row_ids = torch.empty(slots * cfg.batch, dtype=torch.int64, device=d)
+    return B.Tier(host, dev, row_ids, slots, cfg.batch)
+
+
+def test_tiered_m_gives_the_same_bytes_as_resident_m(H):
+    import oracle
+    d = H.dev()
+    cfg = W.gpt2_4bit().scaled(name="tier", n_samples=48, seq=96, epochs=3, shuffle_ids=True)
+    slots = 3
+    stream = W.ActivationStream(cfg)
+    tier = _tier(cfg, slots, d)
+    resident = torch.zeros((cfg.n_samples, cfg.n_per), dtype=torch.float16, device=d)
+    m_host = np.zeros((cfg.n_samples, cfg.n_per), dtype=np.float16)       # the oracle's m
+    compute, copy = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    win_desc = B.make_desc(batch=cfg.batch, n_per=cfg.n_per, n_samples=slots * cfg.batch, bits=4,
+                           group=cfg.fwd_group, dtype="f16")
+    res_desc = B.make_desc(batch=cfg.batch, n_per=cfg.n_per, n_samples=cfg.n_samples, bits=4,
+                           group=cfg.fwd_group, dtype="f16")
+    calls = [(t, k, ids) for t in range(cfg.epochs) for k, ids in enumerate(stream.epoch_ids(t))]
+    keep = []
+    tier.prefetch(0, torch.from_numpy(calls[0][2].copy()), copy)
+    for n, (t, k, ids) in enumerate(calls):
+        slot = n % slots
+        if n + 1 < len(calls):                       # next micro-batch's rows travel while this one computes
+            tier.prefetch((n + 1) % slots, torch.from_numpy(calls[n + 1][2].copy()), copy)
+        act_np = stream.activations(ids, t).reshape(cfg.batch, cfg.n_per)
+        with torch.cuda.stream(compute):
+            act = W.to_torch(act_np, "f16", d)
+            codes = torch.empty(B.codes_bytes(win_desc), dtype=torch.uint8, device=d)
+            scales = torch.empty(B.scales_count(win_desc), dtype=torch.float32, device=d)
+            win_ids = tier.acquire(slot, compute)
+            B.encode(win_desc, act, win_ids, tier.dev_rows, codes, scales, stream=compute)
+            tier.release(slot, compute, copy)
+            # the same call against the resident array
+            codes2 = torch.empty_like(codes)
+            scales2 = torch.empty_like(scales)
+            B.encode(res_desc, act, torch.from_numpy(ids).to(d), resident, codes2, scales2, stream=compute)
+        wc, ws = oracle.encode(act_np, ids, m_host, dtype="f16", bits=4, group=cfg.fwd_group)
+        keep.append((codes, scales, codes2, scales2, wc, ws, act))
+    tier.drain()
+    torch.cuda.synchronize()
+    for n, (codes, scales, codes2, scales2, wc, ws, _) in enumerate(keep):
+        assert H.same_bytes(codes.cpu().numpy(), wc), f"call {n}: tiered codes differ from the oracle"
+        assert H.same_bytes(scales.cpu().numpy(), ws), f"call {n}: tiered scales differ from the oracle"
+        assert torch.equal(codes, codes2) and torch.equal(scales, scales2)
+    assert H.same_bytes(tier.host_rows.numpy(), m_host)                   # host tier is current
+    assert H.same_bytes(resident.cpu().numpy(), m_host)
+    tier.close()
+
+
+def test_tier_protocol_errors(H):
+    d = H.dev()
+    cfg = W.gpt2_4bit().scaled(n_samples=16, seq=8)
+    tier = _tier(cfg, 2, d)
+    s = torch.cuda.Stream()
+    ids = torch.tensor([3, 1, 0, 7], dtype=torch.int64)
+    with pytest.raises(B.AqsgdError) as e:
+        tier.acquire(0, s)                          # nothing prefetched
+    assert e.value.status == -5
+    tier.prefetch(0, ids, s)
+    with pytest.raises(B.AqsgdError):
+        tier.prefetch(0, ids, s)                    # window not released
+    with pytest.raises(B.AqsgdError):
+        tier.prefetch(1, torch.tensor([3, 1, 0, 16], dtype=torch.int64), s)   # id out of range
+    with pytest.raises(B.AqsgdError):
+        tier.release(1, s, s)                       # empty window
+    assert list(tier.acquire(0, s).cpu().numpy()) == [0, 1, 2, 3]
+    tier.release(0, s, s)
+    tier.prefetch(0, ids, s)                        # released: may be filled again
+    tier.release(0, s, s)
+    tier.drain()
+    tier.close()
+
+
+def test_tier_copy_rate_against_the_papers_budget(H, capsys):
+    """The paper hides 0.2 ms of loading per micro-batch behind 44 ms of forward
+    compute.  Here: rows of the GPT2 shape (3.2 MB each, 4 per micro-batch) in and
+    out over the host link; the round trip must be far below that budget."""
+    d = H.dev()
+    cfg = W.gpt2_4bit().scaled(n_samples=256)
+    slots = 4
+    tier = _tier(cfg, slots, d)
+    copy = torch.cuda.Stream()
+    rng = np.random.default_rng(0)
+    perm = rng.permutation(cfg.n_samples).reshape(-1, cfg.batch)
+    torch.cuda.synchronize()
+    reps = len(perm)
+    t0 = time.perf_counter()
+    for n in range(reps):
+        slot = n % slots
+        tier.prefetch(slot, torch.from_numpy(perm[n].copy()), copy)
+        tier.acquire(slot, copy)
+        tier.release(slot, copy, copy)
+    tier.drain()
+    dt = (time.perf_counter() - t0) / reps
+    moved = 2 * cfg.batch * cfg.n_per * 2
+    with capsys.disabled():
+        print(f"\n[tier] {cfg.batch} rows x {cfg.n_per * 2 / 1e6:.2f} MB in and out: {dt * 1e3:.3f} ms per "
+              f"micro-batch, {moved / dt / 1e9:.1f} GB/s over the host link")
+    assert dt < 5e-3            # << 44 ms of forward compute per micro-batch in the paper's setting
+    tier.close()
