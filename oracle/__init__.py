@@ -319,3 +319,42 @@ def decode_lowbit(codes: np.ndarray, scales: np.ndarray, ids: np.ndarray, m_code
     if rc:
         raise ValueError(f"oracle decode_lowbit rejected its arguments (rc={rc})")
     return out
+
+
+# -- sparsified backward message (top-k + b-bit, Appendix H.6) ------------------
+def grad_topk_quant(grad: np.ndarray, *, dtype: str, bits: int, group: int, keep: int,
+                    rounding: int = NEAREST, seed: int = 0):
+    """Returns (bitmap uint8[n/8], codes uint8[n_groups*keep*bits/8], scales float32[n_groups])."""
+    dt = DTYPE_CODE[dtype]
+    _check(grad, _NP_OF[dt], "grad")
+    n = grad.size
+    bitmap = np.zeros(n // 8, dtype=np.uint8)
+    codes = np.zeros(n // group * keep * bits // 8, dtype=np.uint8)
+    scales = np.zeros(n // group, dtype=np.float32)
+    L = lib()
+    L.aqsgd_oracle_grad_topk_quant.restype = ctypes.c_int
+    L.aqsgd_oracle_grad_topk_quant.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                               ctypes.c_int, ctypes.c_uint64, ctypes.c_int64] + [ctypes.c_void_p] * 4
+    rc = L.aqsgd_oracle_grad_topk_quant(dt, bits, group, keep, rounding, seed, n, _ptr(grad), _ptr(bitmap),
+                                        _ptr(codes), _ptr(scales))
+    if rc:
+        raise ValueError(f"oracle grad_topk_quant rejected its arguments (rc={rc})")
+    return bitmap, codes, scales
+
+
+def grad_topk_dequant(bitmap: np.ndarray, codes: np.ndarray, scales: np.ndarray, *, dtype: str,
+                      bits: int, group: int, keep: int) -> np.ndarray:
+    dt = DTYPE_CODE[dtype]
+    _check(bitmap, np.uint8, "bitmap"); _check(codes, np.uint8, "codes"); _check(scales, np.float32, "scales")
+    n = scales.size * group
+    assert bitmap.size == n // 8 and codes.size == scales.size * keep * bits // 8
+    out = np.zeros(n, dtype=_NP_OF[dt])
+    L = lib()
+    L.aqsgd_oracle_grad_topk_dequant.restype = ctypes.c_int
+    L.aqsgd_oracle_grad_topk_dequant.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                                 ctypes.c_int64] + [ctypes.c_void_p] * 4
+    rc = L.aqsgd_oracle_grad_topk_dequant(dt, bits, group, keep, n, _ptr(bitmap), _ptr(codes), _ptr(scales),
+                                          _ptr(out))
+    if rc:
+        raise ValueError(f"oracle grad_topk_dequant rejected its arguments (rc={rc})")
+    return out

@@ -44,8 +44,9 @@
  * invariants (first visit = direct quantisation, replica identity, error
  * bound, unbiasedness, contraction, message size); the uncompressed first
  * visit and the low-precision storage of m (end of this file) against their
- * own invariants and the appendix's ordering of errors.  No function here is
- * "parity unpinned".
+ * own invariants and the appendix's ordering of errors; the sparsified
+ * backward message against the definition of "k largest", the dense message
+ * at keep = G and crafted ties.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -532,6 +533,100 @@ int aqsgd_oracle_decode_lowbit(int dtype, int bits, int m_bits, int64_t group, i
             store_group(v, group, m_bits, half, q, tmp, mc, ms);
         }
         free(m_hat); free(dhat); free(v); free(half); free(tmp); free(q);
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Sparsified backward message ("bw8[0.2]", Appendix H.6: "we keep only */
+/* the top 20% gradients and then perform 8-bit quantization").         */
+/* The appendix says no more; reading: per group of G elements the      */
+/* `keep` entries of largest magnitude survive (equal magnitudes: the    */
+/* lower index first); survivors are quantised by Q_b with the group's   */
+/* max-abs scale (the largest entry always survives), everything else   */
+/* reconstructs as +0.  On the wire, per call: a bitmap with one bit    */
+/* per element (element j at bit j mod 8 of byte j/8), `keep` b-bit     */
+/* levels per group in index order, one scale per group.                */
+/* ------------------------------------------------------------------ */
+typedef struct { float mag; int64_t idx; } oracle_ranked;
+
+static int by_magnitude_then_index(const void* pa, const void* pb)
+{
+    const oracle_ranked* a = pa;
+    const oracle_ranked* b = pb;
+    if (a->mag > b->mag) return -1;
+    if (a->mag < b->mag) return 1;
+    return (a->idx > b->idx) - (a->idx < b->idx);
+}
+
+int aqsgd_oracle_grad_topk_quant(int dtype, int bits, int64_t group, int64_t keep, int rounding,
+                                 uint64_t seed, int64_t n, const void* grad, uint8_t* bitmap,
+                                 uint8_t* codes, float* scales)
+{
+    int rc = check_shape(dtype, bits, group, rounding, 1, n);
+    if (rc) return rc;
+    if (keep < 1 || keep > group || group % 8 || (keep * bits) % 8) return -7;
+    const int64_t n_groups = n / group;
+    memset(bitmap, 0, (size_t)(n / 8));
+#pragma omp parallel
+    {
+        float* d = malloc(sizeof(float) * group);
+        float* r = malloc(sizeof(float) * group);
+        float* dhat = malloc(sizeof(float) * group);
+        int32_t* q = malloc(sizeof(int32_t) * group);
+        int32_t* kept_q = malloc(sizeof(int32_t) * keep);
+        uint8_t* kept = malloc((size_t)group);
+        oracle_ranked* order = malloc(sizeof(oracle_ranked) * group);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t a0 = g * group;
+            for (int64_t e = 0; e < group; ++e) {
+                d[e] = load_elem(grad, a0 + e, dtype);
+                order[e].mag = fabsf(d[e]);
+                order[e].idx = e;
+                kept[e] = 0;
+            }
+            qsort(order, (size_t)group, sizeof(oracle_ranked), by_magnitude_then_index);
+            for (int64_t k = 0; k < keep; ++k) kept[order[k].idx] = 1;
+            rounding_offsets(rounding, seed, a0, group, r);
+            aqsgd_oracle_quantize_group(d, r, group, bits, q, &scales[g], dhat);
+            int64_t pos = 0;
+            for (int64_t e = 0; e < group; ++e)
+                if (kept[e]) {
+                    bitmap[(a0 + e) / 8] |= (uint8_t)(1u << ((a0 + e) % 8));
+                    kept_q[pos++] = q[e];
+                }
+            aqsgd_oracle_pack(kept_q, keep, bits, codes + g * keep * bits / 8);
+        }
+        free(d); free(r); free(dhat); free(q); free(kept_q); free(kept); free(order);
+    }
+    return 0;
+}
+
+int aqsgd_oracle_grad_topk_dequant(int dtype, int bits, int64_t group, int64_t keep, int64_t n,
+                                   const uint8_t* bitmap, const uint8_t* codes, const float* scales,
+                                   void* out)
+{
+    int rc = check_shape(dtype, bits, group, ORACLE_NEAREST, 1, n);
+    if (rc) return rc;
+    if (keep < 1 || keep > group || group % 8 || (keep * bits) % 8) return -7;
+    const int64_t n_groups = n / group;
+#pragma omp parallel
+    {
+        int32_t* kept_q = malloc(sizeof(int32_t) * keep);
+        float* val = malloc(sizeof(float) * keep);
+#pragma omp for schedule(static)
+        for (int64_t g = 0; g < n_groups; ++g) {
+            const int64_t a0 = g * group;
+            aqsgd_oracle_unpack(codes + g * keep * bits / 8, keep, bits, kept_q);
+            aqsgd_oracle_dequantize_group(kept_q, scales[g], keep, bits, val);
+            int64_t pos = 0;
+            for (int64_t e = 0; e < group; ++e) {
+                const int on = (bitmap[(a0 + e) / 8] >> ((a0 + e) % 8)) & 1;
+                store_elem(out, a0 + e, dtype, (on && pos < keep) ? val[pos++] : 0.0f);
+            }
+        }
+        free(kept_q); free(val);
     }
     return 0;
 }
