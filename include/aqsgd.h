@@ -169,6 +169,32 @@ int aqsgd_decode_lowbit(const aqsgd_desc* desc, int32_t m_bits, const uint8_t* c
                         float* m_scales, void* out, void* stream);
 
 /*
+ * Sparsified backward message ("bw8[0.2]", Appendix H.6: only the largest fifth of
+ * the gradient entries is sent, at 8 bits).  The appendix gives no format; here, per
+ * group of `group` consecutive entries, the `keep` entries of largest magnitude are
+ * sent (equal magnitudes: the lower index first) as levels of the same Q with the
+ * group's max-abs scale; every other entry reconstructs as +0.
+ *   desc     bits must be 8 (else AQSGD_ERR_BITS); group a multiple of 8, at most 2048
+ *            (else AQSGD_ERR_GROUP); batch * n_per entries; n_samples unused
+ *   keep     1 .. group (else AQSGD_ERR_SHAPE)
+ *   grad     in   [batch, n_per] of desc.dtype, 16-byte aligned, no NaN
+ *   bitmap   out/in  uint8[batch * n_per / 8]: entry j kept <=> bit j % 8 of byte j / 8
+ *   codes    out/in  uint8[n_groups * keep]: a group's levels in ascending entry order;
+ *            16-byte aligned when keep is a multiple of 16
+ *   scales   out/in  float[n_groups], n_groups = batch * n_per / group
+ *   out      out  [batch, n_per] of desc.dtype
+ * A receiver handed a bitmap with more than `keep` bits in a group returns unspecified
+ * values for that group (no access leaves the buffers).  All pointers are DEVICE
+ * pointers owned by the caller; the calls enqueue on `stream` and return.
+ */
+size_t aqsgd_topk_bitmap_bytes(const aqsgd_desc* desc);
+size_t aqsgd_topk_codes_bytes(const aqsgd_desc* desc, int32_t keep);
+int aqsgd_grad_topk_quant(const aqsgd_desc* desc, int32_t keep, const void* grad, uint8_t* bitmap,
+                          uint8_t* codes, float* scales, void* stream);
+int aqsgd_grad_topk_dequant(const aqsgd_desc* desc, int32_t keep, const uint8_t* bitmap,
+                            const uint8_t* codes, const float* scales, void* out, void* stream);
+
+/*
  * Host-memory tier for the previous messages (Section 3.3, "System Implementations
  * and Optimizations": m(xi) is kept in a local buffer in host memory, loaded to the
  * GPU before the forward pass of its sample and written back after the update, both

@@ -25,7 +25,8 @@ EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_dec
            "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_lowbit_row_bytes",
            "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
            "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
-           "aqsgd_check_ids",
+           "aqsgd_topk_bitmap_bytes", "aqsgd_topk_codes_bytes", "aqsgd_grad_topk_quant",
+           "aqsgd_grad_topk_dequant", "aqsgd_check_ids",
            "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
@@ -75,6 +76,14 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_encode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
         L.aqsgd_decode_lowbit.restype = ctypes.c_int
         L.aqsgd_decode_lowbit.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_topk_bitmap_bytes.restype = ctypes.c_size_t
+        L.aqsgd_topk_bitmap_bytes.argtypes = [dp]
+        L.aqsgd_topk_codes_bytes.restype = ctypes.c_size_t
+        L.aqsgd_topk_codes_bytes.argtypes = [dp, ctypes.c_int32]
+        L.aqsgd_grad_topk_quant.restype = ctypes.c_int
+        L.aqsgd_grad_topk_quant.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp]
+        L.aqsgd_grad_topk_dequant.restype = ctypes.c_int
+        L.aqsgd_grad_topk_dequant.argtypes = [dp, ctypes.c_int32, vp, vp, vp, vp, vp]
         L.aqsgd_tier_create.restype = ctypes.c_int
         L.aqsgd_tier_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_int32]
@@ -188,6 +197,27 @@ def decode_lowbit(desc: Desc, m_bits: int, codes, scales, sample_ids, m_codes, m
                                      _dev(scales, "scales"), _dev(sample_ids, "sample_ids"),
                                      _dev(m_codes, "m_codes"), _dev(m_scales, "m_scales"),
                                      _dev(out, "out"), _stream(stream)))
+
+
+def topk_bitmap_bytes(desc: Desc) -> int:
+    return int(lib().aqsgd_topk_bitmap_bytes(ctypes.byref(desc)))
+
+
+def topk_codes_bytes(desc: Desc, keep: int) -> int:
+    return int(lib().aqsgd_topk_codes_bytes(ctypes.byref(desc), keep))
+
+
+def grad_topk_quant(desc: Desc, keep: int, grad, bitmap, codes, scales, stream=None) -> None:
+    """``aqsgd_grad_topk_quant``: the ``keep`` largest entries per group, at 8 bits."""
+    _raise(lib().aqsgd_grad_topk_quant(ctypes.byref(desc), keep, _dev(grad, "grad"), _dev(bitmap, "bitmap"),
+                                       _dev(codes, "codes"), _dev(scales, "scales"), _stream(stream)))
+
+
+def grad_topk_dequant(desc: Desc, keep: int, bitmap, codes, scales, out, stream=None) -> None:
+    """``aqsgd_grad_topk_dequant``: kept entries reconstructed, the rest +0."""
+    _raise(lib().aqsgd_grad_topk_dequant(ctypes.byref(desc), keep, _dev(bitmap, "bitmap"),
+                                         _dev(codes, "codes"), _dev(scales, "scales"), _dev(out, "out"),
+                                         _stream(stream)))
 
 
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:

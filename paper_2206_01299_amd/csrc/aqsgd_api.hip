@@ -5,6 +5,7 @@
 
 #include "aqsgd_kernels.h"
 #include "aqsgd_lowbit.h"
+#include "aqsgd_topk.h"
 
 namespace aqsgd {
 
@@ -253,6 +254,28 @@ int run_lowbit(const aqsgd_desc* d, int32_t m_bits, bool sender, const void* act
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
+int check_topk(const aqsgd_desc* d, int32_t keep) {
+    const int rc = check_desc(d, false);
+    if (rc != AQSGD_OK) return rc;
+    if (d->bits != kTopkBits) return AQSGD_ERR_BITS;
+    if (d->group % kChunk != 0 || d->group > kTopkMaxGroup) return AQSGD_ERR_GROUP;
+    if (keep < 1 || keep > d->group) return AQSGD_ERR_SHAPE;
+    return AQSGD_OK;
+}
+
+int run_topk(const aqsgd_desc* d, int32_t keep, bool sender, const void* grad, void* out, uint8_t* bitmap,
+             uint8_t* codes, float* scales, hipStream_t stream) {
+    TopkArgs a;
+    a.grad = grad; a.out = out; a.bitmap = bitmap; a.codes = codes; a.scales = scales;
+    a.n_groups = d->batch * (d->n_per / d->group);
+    a.group = d->group; a.cpg = d->group / kChunk; a.keep = keep;
+    a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
+    const int cpl = a.cpg <= kWave ? 1 : (a.cpg <= 2 * kWave ? 2 : 4);
+    const LaunchGeom g = geometry(a.n_groups, kBlock / kWave, 1);
+    const hipError_t err = launch_topk(d->dtype, cpl, sender, g.grid_x, a, stream);
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
 __global__ void check_ids_kernel(const int64_t* ids, int64_t batch, int64_t n_samples, int32_t* flag) {
     int bad = 0;
     for (int64_t i = threadIdx.x + static_cast<int64_t>(blockIdx.x) * blockDim.x; i < batch;
@@ -396,6 +419,39 @@ int aqsgd_decode_lowbit(const aqsgd_desc* d, int32_t m_bits, const uint8_t* code
         return AQSGD_ERR_ALIGN;
     return run_lowbit(d, m_bits, false, nullptr, out, sample_ids, m_codes, m_scales,
                       const_cast<uint8_t*>(codes), const_cast<float*>(scales), static_cast<hipStream_t>(stream));
+}
+
+size_t aqsgd_topk_bitmap_bytes(const aqsgd_desc* d) {
+    if (check_topk(d, 1) != AQSGD_OK) return 0;
+    return static_cast<size_t>(d->batch) * static_cast<size_t>(d->n_per) / 8;
+}
+
+size_t aqsgd_topk_codes_bytes(const aqsgd_desc* d, int32_t keep) {
+    if (check_topk(d, keep) != AQSGD_OK) return 0;
+    return static_cast<size_t>(d->batch) * static_cast<size_t>(d->n_per / d->group) * keep;
+}
+
+int aqsgd_grad_topk_quant(const aqsgd_desc* d, int32_t keep, const void* grad, uint8_t* bitmap,
+                          uint8_t* codes, float* scales, void* stream) {
+    const int rc = check_topk(d, keep);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!grad || !bitmap || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(grad, 16) || !aligned(scales, 4) || (keep % 16 == 0 && !aligned(codes, 16)))
+        return AQSGD_ERR_ALIGN;
+    return run_topk(d, keep, true, grad, nullptr, bitmap, codes, scales, static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_grad_topk_dequant(const aqsgd_desc* d, int32_t keep, const uint8_t* bitmap, const uint8_t* codes,
+                            const float* scales, void* out, void* stream) {
+    const int rc = check_topk(d, keep);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!bitmap || !codes || !scales || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(scales, 4) || (keep % 16 == 0 && !aligned(codes, 16)))
+        return AQSGD_ERR_ALIGN;
+    return run_topk(d, keep, false, nullptr, out, const_cast<uint8_t*>(bitmap), const_cast<uint8_t*>(codes),
+                    const_cast<float*>(scales), static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples, int32_t* flag,
