@@ -89,6 +89,9 @@ def parse_args():
     ap.add_argument("--m-bits", type=int, choices=[0, 2, 8], default=0,
                     help="keep the previous messages as z-bit levels (Appendix H.5) instead of the "
                          "activation dtype; 0 = full precision (the headline configuration)")
+    ap.add_argument("--bwd-keep", type=float, default=0.0,
+                    help="sparsify the backward message (Appendix H.6): fraction of each group's "
+                         "entries that is sent, at 8 bits; 0 = dense (the headline configuration)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
                          "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
@@ -98,7 +101,7 @@ def parse_args():
 class Workload:
     """Device-resident state of the benchmarked boundary."""
 
-    def __init__(self, cfg, pool: int, seed: int = 1234, m_bits: int = 0):
+    def __init__(self, cfg, pool: int, seed: int = 1234, m_bits: int = 0, bwd_keep: float = 0.0):
         import torch
         from paper_2206_01299_amd import binding as B
         self.torch, self.B, self.cfg = torch, B, cfg
@@ -152,6 +155,12 @@ class Workload:
         self.scales = torch.empty((pool, B.scales_count(self.fdesc)), dtype=torch.float32, device=d)
         self.bcodes = torch.empty((pool, B.codes_bytes(self.bdesc)), dtype=torch.uint8, device=d)
         self.bscales = torch.empty((pool, B.scales_count(self.bdesc)), dtype=torch.float32, device=d)
+
+        self.keep = int(round(bwd_keep * cfg.bwd_group)) if bwd_keep else 0
+        if self.keep:   # only the largest entries of each group travel (Appendix H.6)
+            self.bitmap = torch.empty((pool, B.topk_bitmap_bytes(self.bdesc)), dtype=torch.uint8, device=d)
+            self.bcodes = torch.empty((pool, B.topk_codes_bytes(self.bdesc, self.keep)), dtype=torch.uint8,
+                                      device=d)
 
         perm = torch.randperm(cfg.n_samples, generator=g, device=d)
         self.ids = perm.view(-1, Bn).contiguous()              # [calls per epoch, B]
@@ -209,11 +218,19 @@ class Workload:
     def grad_quant(self, k):
         s = k % self.pool
         self.bdesc.rng_seed = 0x5EED0001 + 2 * k
-        self.B.grad_quant(self.bdesc, self.grad[s], self.bcodes[s], self.bscales[s])
+        if self.keep:
+            self.B.grad_topk_quant(self.bdesc, self.keep, self.grad[s], self.bitmap[s], self.bcodes[s],
+                                   self.bscales[s])
+        else:
+            self.B.grad_quant(self.bdesc, self.grad[s], self.bcodes[s], self.bscales[s])
 
     def grad_dequant(self, k):
         s = k % self.pool
-        self.B.grad_dequant(self.bdesc, self.bcodes[s], self.bscales[s], self.gout[s])
+        if self.keep:
+            self.B.grad_topk_dequant(self.bdesc, self.keep, self.bitmap[s], self.bcodes[s], self.bscales[s],
+                                     self.gout[s])
+        else:
+            self.B.grad_dequant(self.bdesc, self.bcodes[s], self.bscales[s], self.gout[s])
 
     LEGS = ("encode", "decode", "grad_quant", "grad_dequant")
 
@@ -256,6 +273,8 @@ class Workload:
         fs, bs = 4.0 * n / c.fwd_group, 4.0 * n / c.bwd_group
         M = self.m_bits / 8.0 if self.m_bits else E   # bytes per element of the stored m
         ss = 2 * fs if self.m_bits else 0.0           # storage scales, read and written
+        if self.keep:                                 # a bit per entry + a byte per kept entry
+            bb = 1.0 / 8.0 + self.keep / c.bwd_group
         return {
             "encode": n * (E + M + M + fb) + fs + ss,     # act, m read, m write, codes + scales
             "decode": n * (fb + M + M + E) + fs + ss,     # codes, m read, m write, out + scales
@@ -409,7 +428,7 @@ def main():
     if args.pool <= 0:
         args.pool = max(4, -(-1_250_000_000 // (cfg.n * cfg.elem_bytes)))
     t_setup = time.perf_counter()
-    wl = Workload(cfg, args.pool, m_bits=args.m_bits)
+    wl = Workload(cfg, args.pool, m_bits=args.m_bits, bwd_keep=args.bwd_keep)
     wl.preseed_and_drift()
     t_setup = time.perf_counter() - t_setup
 
@@ -440,7 +459,8 @@ def main():
     if legs:
         dominant = max(wl.LEGS, key=lambda l: legs[l]["avg_us"])
         a_gbps = lb[dominant] / (legs[dominant]["avg_us"] * 1e-6) / 1e9
-        traffic = read_traffic() if args.config == "gpt2_4bit" and not args.m_bits else None
+        traffic = (read_traffic() if args.config == "gpt2_4bit" and not args.m_bits and not args.bwd_keep
+                   else None)
         roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(a_gbps, 1),
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
                     "algorithmic_bytes_per_launch": lb[dominant],
@@ -480,7 +500,8 @@ def main():
                    "name": cfg.name,
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
-                   "group": cfg.fwd_group, "m_bits": args.m_bits or None, "pool_slots": args.pool, "launch": args.launch,
+                   "group": cfg.fwd_group, "m_bits": args.m_bits or None, "bwd_keep": args.bwd_keep or None,
+                   "pool_slots": args.pool, "launch": args.launch,
                    "streams": args.streams,
                    "cold_buffers": True, "device": torch.cuda.get_device_name(0),
                    "setup_s": round(t_setup, 1)},

@@ -3,14 +3,16 @@
 // levels of Q with the group's max-abs scale, plus one bit per entry that says
 // which ones.  Equal magnitudes: the lower index survives first.
 //
-// One wave owns a group (G <= 2048).  The threshold is the keep-th largest
-// magnitude, found on the magnitudes' bit patterns (which order like unsigned
-// integers) by building it bit by bit from the top: a bit stays set if at least
-// `keep` entries are >= the candidate.  Every count is a wave ballot and a scalar
-// population count, so a pass costs one vector compare per entry held by a lane.
-// Positions in the compacted byte string come from the same ballots through
-// mbcnt (set bits in lower lanes).  The kept bytes are gathered in LDS and leave
-// as full-width stores; the receiver stages them the same way.
+// One wave owns a group (G <= 2048) and keeps it in registers.  The threshold is
+// the keep-th largest magnitude, found on the magnitudes' bit patterns (which
+// order like unsigned integers) by a radix select, one byte per level: the wave
+// histograms the byte in 256 LDS counters, a prefix sum over the lanes (each
+// holding four counters) finds the counter that contains the wanted rank, and the
+// next level only looks at entries that share the bytes decided so far.  Two
+// levels for the 16-bit types, four for binary32.  Positions in the compacted
+// byte string come from per-lane population counts and the same wave prefix sum.
+// The kept bytes are gathered in LDS and leave as full-width stores; the receiver
+// stages them the same way.
 #pragma once
 
 #include "aqsgd_kernels.h"
@@ -33,36 +35,35 @@ struct TopkArgs {
 
 constexpr int kTopkMaxGroup = 2048;
 constexpr int kTopkBits = 8;
+constexpr int kTopkBins = 256;
+constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per lane for entries not kept
 
-// Number of magnitude bits that can differ between two entries of the dtype.
-template <int DT> struct KeyBits { static constexpr int value = 15; };
-template <> struct KeyBits<AQSGD_F32> { static constexpr int value = 31; };
+// LDS of one wave.
+struct TopkLds {
+    uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
+    uint8_t stage[kTopkStageBytes];
+};
 
-// Magnitude bit patterns of a chunk, straight from storage: the 15 low bits of a
-// half or bfloat16, the 31 low bits of a binary32.
+// Bytes of a magnitude key: the key is the magnitude's bit pattern shifted left by
+// one, so it fills 2 (half, bfloat16) or 4 (binary32) whole bytes.
+template <int DT> struct KeyBytes { static constexpr int value = 2; };
+template <> struct KeyBytes<AQSGD_F32> { static constexpr int value = 4; };
+
 template <int DT>
 __device__ __forceinline__ void magnitude_keys(const Raw<DT>& r, uint32_t (&u)[kChunk]) {
     if constexpr (DT == AQSGD_F32) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            u[i] = __float_as_uint(r.lo[i]) & 0x7fffffffu;
-            u[4 + i] = __float_as_uint(r.hi[i]) & 0x7fffffffu;
+            u[i] = __float_as_uint(r.lo[i]) << 1;
+            u[4 + i] = __float_as_uint(r.hi[i]) << 1;
         }
     } else {
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            u[2 * i] = r.v[i] & 0x7fffu;
-            u[2 * i + 1] = (r.v[i] >> 16) & 0x7fffu;
+            u[2 * i] = (r.v[i] << 1) & 0xfffeu;
+            u[2 * i + 1] = (r.v[i] >> 15) & 0xfffeu;
         }
     }
-}
-
-__device__ __forceinline__ int wave_count(uint64_t ballot) { return __builtin_popcountll(ballot); }
-
-// acc + number of set ballot bits that belong to lower lanes
-__device__ __forceinline__ uint32_t lower_lanes(uint64_t ballot, uint32_t acc) {
-    return __builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(ballot >> 32),
-                                     __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(ballot), acc));
 }
 
 // LDS traffic of one wave: later reads must see earlier writes of other lanes.
@@ -72,9 +73,124 @@ __device__ __forceinline__ void wave_lds_sync() {
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
 }
 
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_shifted_or_zero(uint32_t v) {
+    // lanes without a source lane in their row of 16 read zero
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+}
+
+// Inclusive prefix sum over the 64 lanes (lane order); `total` = the sum of all lanes.
+__device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x, int lane, uint32_t& total) {
+    x += dpp_shifted_or_zero<0x111>(x);                  // row_shr:1
+    x += dpp_shifted_or_zero<0x112>(x);                  // row_shr:2
+    x += dpp_shifted_or_zero<0x114>(x);                  // row_shr:4
+    x += dpp_shifted_or_zero<0x118>(x);                  // row_shr:8 -> prefix within each row of 16
+    const uint32_t r0 = __builtin_amdgcn_readlane(x, 15);
+    const uint32_t r1 = __builtin_amdgcn_readlane(x, 31);
+    const uint32_t r2 = __builtin_amdgcn_readlane(x, 47);
+    const uint32_t r3 = __builtin_amdgcn_readlane(x, 63);
+    total = r0 + r1 + r2 + r3;
+    const uint32_t before = lane < 16 ? 0u : (lane < 32 ? r0 : (lane < 48 ? r0 + r1 : r0 + r1 + r2));
+    return x + before;
+}
+
+// The keep-th largest key of the group and how many entries equal to it are kept.
+// `equal_total` = number of entries equal to the threshold.
+template <int DT, int CPL>
+__device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], const bool (&valid)[CPL],
+                                            int keep, int lane, uint32_t* bins, uint32_t& threshold,
+                                            int& equal_kept, int& equal_total) {
+    uint32_t prefix = 0;                                 // bytes of the threshold decided so far
+    uint32_t need = static_cast<uint32_t>(keep);         // rank of the threshold among entries sharing them
+    uint32_t in_bin = 0;
+#pragma unroll
+    for (int level = KeyBytes<DT>::value - 1; level >= 0; --level) {
+        const int shift = 8 * level;
+        u32x4_t zero = {0u, 0u, 0u, 0u};
+        *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
+        wave_lds_sync();
+        // Below the top level only entries that share the decided bytes count.  With
+        // those bytes cancelled by an exclusive-or, a sharing entry is left with its
+        // byte (< 256) and every other entry with something larger, which min() sends
+        // to one of the lane's spare counters behind the 256 real ones (never read).
+        const uint32_t decided = level == KeyBytes<DT>::value - 1 ? 0u : prefix << ((shift + 8) & 31);
+#pragma unroll
+        for (int k = 0; k < CPL; ++k)
+            if (valid[k]) {
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e) {
+                    const uint32_t digit = (u[k][e] ^ decided) >> shift;
+                    atomicAdd(&bins[min(digit, static_cast<uint32_t>(kTopkBins + lane))], 1u);
+                }
+            }
+        wave_lds_sync();
+        const u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
+        const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+        uint32_t total;
+        const uint32_t upto = wave_inclusive_sum(mine, lane, total);
+        // entries in counters above this lane's four, then above each of its counters
+        const uint32_t a3 = total - upto;
+        const uint32_t a2 = a3 + c[3], a1 = a2 + c[2], a0 = a1 + c[1];
+        const bool here = a3 < need && need <= a3 + mine;            // exactly one lane
+        const int sel = need <= a2 ? 3 : (need <= a1 ? 2 : (need <= a0 ? 1 : 0));
+        const uint32_t above = sel == 3 ? a3 : (sel == 2 ? a2 : (sel == 1 ? a1 : a0));
+        const uint32_t count = sel == 3 ? c[3] : (sel == 2 ? c[2] : (sel == 1 ? c[1] : c[0]));
+        const uint64_t who = __ballot(here);
+        const int src = who ? __builtin_ctzll(who) : 0;
+        const uint32_t digit = __builtin_amdgcn_readlane(static_cast<uint32_t>(4 * lane + sel), src);
+        need -= __builtin_amdgcn_readlane(above, src);
+        in_bin = __builtin_amdgcn_readlane(count, src);
+        prefix = (prefix << 8) | digit;
+    }
+    threshold = prefix;
+    equal_kept = static_cast<int>(need);
+    equal_total = static_cast<int>(in_bin);
+}
+
+// Bit e of the result: key e is greater than (STRICT) / at least the threshold.
+template <int DT, bool STRICT>
+__device__ __forceinline__ uint32_t chunk_mask(const uint32_t (&u)[kChunk], uint32_t t) {
+    uint32_t m = 0;
+    if constexpr (KeyBytes<DT>::value == 2) {
+        // Keys below 2^16: the sign bit of a difference is the comparison, and alignbit
+        // shifts it into the mask ((m << 1) | (d >> 31)), last entry first.
+#pragma unroll
+        for (int e = kChunk - 1; e >= 0; --e) {
+            const uint32_t d = STRICT ? t - u[e] : u[e] - t;          // sign set: u > t / u < t
+            m = __builtin_amdgcn_alignbit(m, d, 31);
+        }
+        return STRICT ? m : ~m & 0xffu;
+    } else {
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e)
+            m |= static_cast<uint32_t>(STRICT ? u[e] > t : u[e] >= t) << e;
+        return m;
+    }
+}
+
+// Exclusive prefix over the lanes of up to four per-lane counts (each < 2^16 in
+// total), two per scanned register; totals[k] = sum over all lanes.
+template <int CPL>
+__device__ __forceinline__ void lanes_before(const uint32_t (&cnt)[CPL], int lane, uint32_t (&before)[CPL],
+                                             uint32_t (&totals)[CPL]) {
+#pragma unroll
+    for (int k = 0; k < CPL; k += 2) {
+        const int k1 = k + 1 < CPL ? k + 1 : k;         // second count of the pair, if there is one
+        const uint32_t packed = cnt[k] | (k1 != k ? cnt[k1] << 16 : 0u);
+        uint32_t tot;
+        const uint32_t excl = wave_inclusive_sum(packed, lane, tot) - packed;
+        before[k] = excl & 0xffffu;
+        totals[k] = tot & 0xffffu;
+        if (k1 != k) {
+            before[k1] = excl >> 16;
+            totals[k1] = tot >> 16;
+        }
+    }
+}
+
 template <int DT, int CPL>
 __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
-                                                 const bool (&valid)[CPL], int lane, uint8_t* stage) {
+                                                 const bool (&valid)[CPL], int lane, TopkLds& lds) {
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
     const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
@@ -93,69 +209,62 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         unpack_raw<DT>(raw[k], f[k]);
         magnitude_keys<DT>(raw[k], u[k]);
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            mx = __builtin_fmaxf(mx, __builtin_fabsf(f[k][e]));      // a clamped lane repeats a real chunk
-            if (!valid[k]) u[k][e] = 0;                               // ... and must not be counted
-        }
+        for (int e = 0; e < kChunk; ++e)                 // a clamped lane repeats a real chunk: harmless here
+            mx = __builtin_fmaxf(mx, __builtin_fabsf(f[k][e]));
     }
     mx = team_max<kWave>(mx);
     const GroupScale sc = make_scale<kTopkBits>(mx);
 
-    // ---- threshold: the keep-th largest key -----------------------------------------
-    uint32_t threshold = 0;
-    for (int b = KeyBits<DT>::value - 1; b >= 0; --b) {
-        const uint32_t candidate = threshold | (1u << b);
-        int at_least = 0;
-#pragma unroll
-        for (int k = 0; k < CPL; ++k)
-#pragma unroll
-            for (int e = 0; e < kChunk; ++e) at_least += wave_count(__ballot(u[k][e] >= candidate));
-        if (at_least >= a.keep) threshold = candidate;
-    }
-    int above = 0;
-#pragma unroll
-    for (int k = 0; k < CPL; ++k)
-#pragma unroll
-        for (int e = 0; e < kChunk; ++e) above += wave_count(__ballot(u[k][e] > threshold));
-    int ties_left = a.keep - above;                      // entries equal to the threshold still to keep
+    uint32_t threshold;
+    int equal_kept, equal_total;
+    kth_largest<DT, CPL>(u, valid, a.keep, lane, lds.bins, threshold, equal_kept, equal_total);
 
-    // ---- keep flags, positions, levels -------------------------------------------------
-    int kept_before = 0;                                 // kept entries of earlier chunk rows
+    // ---- keep flags: everything above the threshold, and the first equal_kept entries equal to it
+    uint32_t geb[CPL];                                   // bit e: entry e is >= the threshold
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        uint32_t gtb = 0, eqb = 0, ties_below = 0;
-        int ties_here = 0;
+        geb[k] = chunk_mask<DT, false>(u[k], threshold);
+        if (!valid[k]) geb[k] = 0;
+    }
+    uint32_t keepb[CPL];
+    if (equal_kept == equal_total) {                     // no choice to make among equals (wave-uniform)
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            const bool gt = u[k][e] > threshold;
-            const bool eq = valid[k] && u[k][e] == threshold;
-            gtb |= static_cast<uint32_t>(gt) << e;
-            eqb |= static_cast<uint32_t>(eq) << e;
-            const uint64_t m = __ballot(eq);
-            ties_below = lower_lanes(m, ties_below);
-            ties_here += wave_count(m);
-        }
-        const int allowed = ties_left - static_cast<int>(ties_below);   // ties this lane may still keep
-        uint32_t keepb = gtb;
-        int seen = 0;
+        for (int k = 0; k < CPL; ++k) keepb[k] = geb[k];
+    } else {
+        uint32_t gtb[CPL], eqb[CPL], ties[CPL], ties_below[CPL], ties_total[CPL];
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            const bool eq = (eqb >> e) & 1u;
-            if (eq && seen < allowed) keepb |= 1u << e;
-            seen += eq;
+        for (int k = 0; k < CPL; ++k) {
+            gtb[k] = chunk_mask<DT, true>(u[k], threshold) & geb[k];
+            eqb[k] = geb[k] & ~gtb[k];
+            ties[k] = __builtin_popcount(eqb[k]);
         }
-        ties_left = max(ties_left - ties_here, 0);
+        lanes_before<CPL>(ties, lane, ties_below, ties_total);
+        int left = equal_kept;                           // equals still to keep when chunk row k starts
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            const int allowed = left - static_cast<int>(ties_below[k]);   // ... when this lane's chunk starts
+            uint32_t kb = gtb[k];
+            int seen = 0;
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) {
+                const uint32_t eq = (eqb[k] >> e) & 1u;
+                if (eq && seen < allowed) kb |= 1u << e;
+                seen += static_cast<int>(eq);
+            }
+            keepb[k] = kb;
+            left = max(left - static_cast<int>(ties_total[k]), 0);
+        }
+    }
 
-        uint32_t kept_below = 0;
-        int kept_here = 0;
+    // ---- positions in the group's byte string, levels, staging ------------------------------
+    uint32_t kept[CPL], kept_below[CPL], kept_total[CPL];
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            const uint64_t m = __ballot((keepb >> e) & 1u);
-            kept_below = lower_lanes(m, kept_below);
-            kept_here += wave_count(m);
-        }
-        uint32_t pos = static_cast<uint32_t>(kept_before) + kept_below;
-
+    for (int k = 0; k < CPL; ++k) kept[k] = __builtin_popcount(keepb[k]);
+    lanes_before<CPL>(kept, lane, kept_below, kept_total);
+    uint32_t row_start = 0;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        uint32_t pos = row_start + kept_below[k];
         float r[kChunk];
         if (a.stochastic) {
             chunk_uniforms(a.seed, static_cast<uint64_t>(e0) + static_cast<uint64_t>(cc[k]) * kChunk, r);
@@ -165,14 +274,16 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         }
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
+            // the upper clamp of the stochastic form is a no-op for r = 1/2
             const float q = level_of<kTopkBits, AQSGD_ROUND_STOCHASTIC>(f[k][e], sc, r[e]);
-            if ((keepb >> e) & 1u) {
-                stage[pos] = static_cast<uint8_t>(static_cast<uint32_t>(q));
-                ++pos;
-            }
+            const uint32_t on = (keepb[k] >> e) & 1u;
+            // entries that are not kept write this lane's spare byte
+            lds.stage[on ? pos : static_cast<uint32_t>(kTopkMaxGroup + lane)] =
+                static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_u8_f32(q, 0, 0));
+            pos += on;
         }
-        if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb);
-        kept_before += kept_here;
+        if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb[k]);
+        row_start += kept_total[k];
     }
 
     // ---- the group's bytes leave LDS ------------------------------------------------------
@@ -180,9 +291,9 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
     uint8_t* dst = a.codes + g * a.keep;
     if (a.keep % 16 == 0) {
         for (int i = lane; i < a.keep / 16; i += kWave)
-            *reinterpret_cast<u32x4_t*>(dst + 16 * i) = *reinterpret_cast<const u32x4_t*>(stage + 16 * i);
+            *reinterpret_cast<u32x4_t*>(dst + 16 * i) = *reinterpret_cast<const u32x4_t*>(lds.stage + 16 * i);
     } else {
-        for (int i = lane; i < a.keep; i += kWave) dst[i] = stage[i];
+        for (int i = lane; i < a.keep; i += kWave) dst[i] = lds.stage[i];
     }
     if (lane == 0) a.scales[g] = sc.s_tx;
     wave_lds_sync();                                     // the next group reuses the staging bytes
@@ -190,7 +301,7 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
 
 template <int DT, int CPL>
 __device__ __forceinline__ void topk_dequant_group(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
-                                                   const bool (&valid)[CPL], int lane, uint8_t* stage) {
+                                                   const bool (&valid)[CPL], int lane, TopkLds& lds) {
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
     const int64_t e0 = g * a.group;
@@ -203,37 +314,36 @@ __device__ __forceinline__ void topk_dequant_group(const TopkArgs& a, int64_t g,
     const uint8_t* src = a.codes + g * a.keep;
     if (a.keep % 16 == 0) {
         for (int i = lane; i < a.keep / 16; i += kWave)
-            *reinterpret_cast<u32x4_t*>(stage + 16 * i) = *reinterpret_cast<const u32x4_t*>(src + 16 * i);
+            *reinterpret_cast<u32x4_t*>(lds.stage + 16 * i) = *reinterpret_cast<const u32x4_t*>(src + 16 * i);
     } else {
-        for (int i = lane; i < a.keep; i += kWave) stage[i] = src[i];
+        for (int i = lane; i < a.keep; i += kWave) lds.stage[i] = src[i];
     }
     wave_lds_sync();
 
     const GroupScale sc = scale_from_wire<kTopkBits>(s_tx);
-    int kept_before = 0;
+    uint32_t kept[CPL], kept_below[CPL], kept_total[CPL];
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        const uint32_t mine = valid[k] ? bm[k] : 0u;
-        uint32_t kept_below = 0;
-        int kept_here = 0;
+        if (!valid[k]) bm[k] = 0;
+        kept[k] = __builtin_popcount(bm[k]);
+    }
+    lanes_before<CPL>(kept, lane, kept_below, kept_total);
+    uint32_t row_start = 0;
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            const uint64_t m = __ballot((mine >> e) & 1u);
-            kept_below = lower_lanes(m, kept_below);
-            kept_here += wave_count(m);
-        }
-        uint32_t pos = static_cast<uint32_t>(kept_before) + kept_below;
+    for (int k = 0; k < CPL; ++k) {
+        uint32_t pos = row_start + kept_below[k];
         float x[kChunk];
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
-            x[e] = 0.0f;
-            if ((mine >> e) & 1u) {
-                x[e] = value_of(static_cast<float>(stage[pos]), sc);   // pos < G <= the staging bytes
-                ++pos;
-            }
+            const uint32_t on = (bm[k] >> e) & 1u;
+            // pos never passes the number of set bits of the group (<= G), so the read stays
+            // inside the staging bytes even for a bitmap that disagrees with `keep`
+            const float v = value_of(static_cast<float>(lds.stage[pos]), sc);
+            x[e] = on ? v : 0.0f;
+            pos += on;
         }
         if (valid[k]) store_raw_at<DT>(dst + cc[k] * kChunkBytes, pack_raw<DT>(x));
-        kept_before += kept_here;
+        row_start += kept_total[k];
     }
     wave_lds_sync();
 }
@@ -242,7 +352,7 @@ template <int DT, int CPL, bool SENDER>
 __global__ __launch_bounds__(kBlock)
 void topk_kernel(const TopkArgs a) {
     constexpr int kWaves = kBlock / kWave;
-    __shared__ __align__(16) uint8_t stage_all[kWaves][kTopkMaxGroup];
+    __shared__ __align__(16) TopkLds lds_all[kWaves];
 
     const int lane = threadIdx.x % kWave;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -256,8 +366,8 @@ void topk_kernel(const TopkArgs a) {
     }
     for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave; g < a.n_groups;
          g += static_cast<int64_t>(gridDim.x) * kWaves) {
-        if constexpr (SENDER) topk_quant_group<DT, CPL>(a, g, cc, valid, lane, stage_all[wave]);
-        else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, stage_all[wave]);
+        if constexpr (SENDER) topk_quant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+        else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
     }
 }
 
