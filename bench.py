@@ -331,6 +331,39 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True):
     return time.perf_counter() - t0
 
 
+def hot_forward_pairs(wl, k, count):
+    """Footnote figure: the same forward pair (same samples, same pool slot) over and
+    over on one stream, so its rows stay in the last-level cache.  Seconds per pair."""
+    torch = wl.torch
+    main = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=main):
+        for _ in range(count):
+            wl.step(k, backward=False)
+    g.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    g.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / count
+
+
+def stream_copy_ceiling(torch, nbytes=1 << 30, reps=5):
+    """Same-run achievable ceiling: a plain device-to-device copy of `nbytes`
+    (read + written bytes per second, GB/s)."""
+    src = torch.empty(nbytes // 2, dtype=torch.float16, device="cuda:0").normal_()
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    a.record()
+    for _ in range(reps):
+        dst.copy_(src)
+    b.record()
+    torch.cuda.synchronize()
+    return 2.0 * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9
+
+
 def kernel_legs(wl, first, count):
     """Per-launch device durations of every leg over `count` steps (HIP events
     stamped by the launch itself, on the stream the kernel runs on)."""
@@ -385,8 +418,18 @@ def cpu_baseline(cfg, calls):
         cpu.forward(acts[i % 2], ids, i)
         cpu.backward(grad, i)
     dt = (time.perf_counter() - t0) / calls
+    oracle.set_threads(1)                                          # the same step on one thread
+    one_calls = max(1, min(8, int(5.0 / max(dt * threads, 1e-3))))
+    t0 = time.perf_counter()
+    for i in range(one_calls):
+        cpu.forward(acts[i % 2], ids, calls + i)
+        cpu.backward(grad, calls + i)
+    dt1 = (time.perf_counter() - t0) / one_calls
+    oracle.set_threads(threads)
     return {"value": cfg.n * cfg.elem_bytes / dt / 1e9, "unit": "GB/s", "cores": threads,
             "kind": "oracle", "ms_per_step": dt * 1e3,
+            "one_thread": {"value": round(cfg.n * cfg.elem_bytes / dt1 / 1e9, 4),
+                           "ms_per_step": round(dt1 * 1e3, 1), "steps": one_calls},
             "sample": f"{calls} full-shape steps (encode+decode+grad_quant+grad_dequant) of "
                       f"{cfg.name}, 1 micro-batch of {cfg.batch} samples revisited, OpenMP over groups"}
 
@@ -483,6 +526,11 @@ def main():
     step_bytes = sum(lb.values())
     extra["step_hbm_GBps"] = round(step_bytes / (wall / K) / 1e9, 1)
     extra["step_frac_of_hbm_peak"] = round(step_bytes / (wall / K) / 1e9 / HBM_PEAK_GBPS, 4)
+    hot = hot_forward_pairs(wl, Wm, 256)
+    extra["fwd_hot_buffers_footnote"] = {"us_per_microbatch": round(hot * 1e6, 3),
+                                         "note": "one micro-batch repeated on one stream: rows stay in the "
+                                                 "last-level cache; not the headline"}
+    extra["stream_copy_ceiling_GBps"] = round(stream_copy_ceiling(torch), 1)
 
     base = None
     if not args.no_cpu_baseline:
