@@ -358,3 +358,60 @@ def grad_topk_dequant(bitmap: np.ndarray, codes: np.ndarray, scales: np.ndarray,
     if rc:
         raise ValueError(f"oracle grad_topk_dequant rejected its arguments (rc={rc})")
     return out
+
+
+# -- Algorithm 1 with its first-visit branch --------------------------------------
+def _seen_args(ids, m_buf, seen):
+    ids = np.ascontiguousarray(ids, dtype=np.int64)
+    assert m_buf.ndim >= 2, "m_buf must be [rows, ...sample shape]"
+    n_rows = m_buf.shape[0]
+    _check(seen, np.uint8, "seen")
+    assert seen.size == n_rows
+    assert ids.size == 0 or (ids.min() >= 0 and ids.max() < n_rows), "sample id out of range"
+    assert len(np.unique(ids)) == ids.size, "duplicate sample ids in one call"
+    return ids, m_buf.size // n_rows
+
+
+def encode_seen(act: np.ndarray, ids: np.ndarray, m_buf: np.ndarray, seen: np.ndarray, *, dtype: str,
+                bits: int, group: int, rounding: int = NEAREST, seed: int = 0, fill: int = 0):
+    """Sender side of Algorithm 1.  Updates ``m_buf`` and ``seen`` in place; returns
+    (first int32[batch], codes, scales); slices of first-visit samples keep ``fill``."""
+    dt = DTYPE_CODE[dtype]
+    _check(act, _NP_OF[dt], "act"); _check(m_buf, _NP_OF[dt], "m_buf")
+    ids, n_per = _seen_args(ids, m_buf, seen)
+    batch = ids.size
+    assert act.size == batch * n_per
+    n = batch * n_per
+    codes = np.full(codes_bytes(n, bits), fill, dtype=np.uint8)
+    scales = np.full(n // group, float(fill), dtype=np.float32)
+    first = np.zeros(batch, dtype=np.int32)
+    L = lib()
+    L.aqsgd_oracle_encode_seen.restype = ctypes.c_int
+    L.aqsgd_oracle_encode_seen.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int,
+                                           ctypes.c_uint64, ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 7
+    rc = L.aqsgd_oracle_encode_seen(dt, bits, group, rounding, seed, batch, n_per, _ptr(act), _ptr(ids),
+                                    _ptr(m_buf), _ptr(seen), _ptr(first), _ptr(codes), _ptr(scales))
+    if rc:
+        raise ValueError(f"oracle encode_seen rejected its arguments (rc={rc})")
+    return first, codes, scales
+
+
+def decode_seen(codes: np.ndarray, scales: np.ndarray, full: np.ndarray, ids: np.ndarray, m_buf: np.ndarray,
+                seen: np.ndarray, *, dtype: str, bits: int, group: int) -> np.ndarray:
+    """Receiver side of Algorithm 1.  Updates ``m_buf`` and ``seen`` in place; returns out."""
+    dt = DTYPE_CODE[dtype]
+    _check(codes, np.uint8, "codes"); _check(scales, np.float32, "scales")
+    _check(full, _NP_OF[dt], "full"); _check(m_buf, _NP_OF[dt], "m_buf")
+    ids, n_per = _seen_args(ids, m_buf, seen)
+    batch = ids.size
+    assert full.size == batch * n_per and scales.size == batch * n_per // group
+    out = np.zeros(batch * n_per, dtype=_NP_OF[dt])
+    L = lib()
+    L.aqsgd_oracle_decode_seen.restype = ctypes.c_int
+    L.aqsgd_oracle_decode_seen.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                           ctypes.c_int64] + [ctypes.c_void_p] * 7
+    rc = L.aqsgd_oracle_decode_seen(dt, bits, group, batch, n_per, _ptr(codes), _ptr(scales), _ptr(full),
+                                    _ptr(ids), _ptr(m_buf), _ptr(seen), _ptr(out))
+    if rc:
+        raise ValueError(f"oracle decode_seen rejected its arguments (rc={rc})")
+    return out

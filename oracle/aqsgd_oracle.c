@@ -46,7 +46,9 @@
  * visit and the low-precision storage of m (end of this file) against their
  * own invariants and the appendix's ordering of errors; the sparsified
  * backward message against the definition of "k largest", the dense message
- * at keep = G and crafted ties.  No function here is "parity unpinned".
+ * at keep = G and crafted ties; Algorithm 1's first-visit branch against
+ * "uncompressed on both machines", the plain encoder on seen samples and
+ * replica identity.  No function here is "parity unpinned".
  */
 #include <math.h>
 #include <stdint.h>
@@ -628,5 +630,91 @@ int aqsgd_oracle_grad_topk_dequant(int dtype, int bits, int64_t group, int64_t k
         }
         free(kept_q); free(val);
     }
+    return 0;
+}
+
+/* ------------------------------------------------------------------ */
+/* Algorithm 1 with its first-visit branch ("if xi not seen before":   */
+/* the activation travels uncompressed and m(xi) <- a(xi); otherwise   */
+/* the change is quantised).  seen[id] != 0 marks samples that have a   */
+/* previous message.  Sender: first[i] = 1 tells the caller that row i  */
+/* of act is the message of sample i and that the sample's slices of    */
+/* codes / scales were not written.  Receiver: `full` holds those rows  */
+/* (rows of samples that were seen before are not read).  Both sides    */
+/* mark the call's samples as seen, so their flags stay identical.      */
+/* ------------------------------------------------------------------ */
+int aqsgd_oracle_encode_seen(int dtype, int bits, int64_t group, int rounding, uint64_t seed,
+                             int64_t batch, int64_t n_per, const void* act, const int64_t* ids,
+                             void* m_buf, uint8_t* seen, int32_t* first, uint8_t* codes,
+                             float* scales)
+{
+    int rc = check_shape(dtype, bits, group, rounding, batch, n_per);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    float* d = malloc(sizeof(float) * group);
+    float* m_old = malloc(sizeof(float) * group);
+    float* r = malloc(sizeof(float) * group);
+    float* dhat = malloc(sizeof(float) * group);
+    int32_t* q = malloc(sizeof(int32_t) * group);
+    for (int64_t i = 0; i < batch; ++i) {
+        const int64_t id = ids[i];
+        if (!seen[id]) {                              /* first visit: full precision */
+            for (int64_t e = 0; e < n_per; ++e)
+                store_elem(m_buf, id * n_per + e, dtype, load_elem(act, i * n_per + e, dtype));
+            first[i] = 1;
+            seen[id] = 1;
+            continue;
+        }
+        first[i] = 0;
+        for (int64_t gs = 0; gs < groups_per_sample; ++gs) {
+            const int64_t a0 = i * n_per + gs * group;    /* flat index in the call */
+            const int64_t m0 = id * n_per + gs * group;
+            for (int64_t e = 0; e < group; ++e) {
+                m_old[e] = load_elem(m_buf, m0 + e, dtype);
+                d[e] = load_elem(act, a0 + e, dtype) - m_old[e];
+            }
+            rounding_offsets(rounding, seed, a0, group, r);
+            aqsgd_oracle_quantize_group(d, r, group, bits, q, &scales[a0 / group], dhat);
+            for (int64_t e = 0; e < group; ++e)
+                store_elem(m_buf, m0 + e, dtype, m_old[e] + dhat[e]);
+            aqsgd_oracle_pack(q, group, bits, codes + a0 * bits / 8);
+        }
+    }
+    free(d); free(m_old); free(r); free(dhat); free(q);
+    return 0;
+}
+
+int aqsgd_oracle_decode_seen(int dtype, int bits, int64_t group, int64_t batch, int64_t n_per,
+                             const uint8_t* codes, const float* scales, const void* full,
+                             const int64_t* ids, void* m_buf, uint8_t* seen, void* out)
+{
+    int rc = check_shape(dtype, bits, group, ORACLE_NEAREST, batch, n_per);
+    if (rc) return rc;
+    const int64_t groups_per_sample = n_per / group;
+    float* dhat = malloc(sizeof(float) * group);
+    int32_t* q = malloc(sizeof(int32_t) * group);
+    for (int64_t i = 0; i < batch; ++i) {
+        const int64_t id = ids[i];
+        if (!seen[id]) {
+            for (int64_t e = 0; e < n_per; ++e) {
+                const float a = load_elem(full, i * n_per + e, dtype);
+                store_elem(m_buf, id * n_per + e, dtype, a);
+                store_elem(out, i * n_per + e, dtype, a);
+            }
+            seen[id] = 1;
+            continue;
+        }
+        for (int64_t gs = 0; gs < groups_per_sample; ++gs) {
+            const int64_t a0 = i * n_per + gs * group;
+            const int64_t m0 = id * n_per + gs * group;
+            aqsgd_oracle_unpack(codes + a0 * bits / 8, group, bits, q);
+            aqsgd_oracle_dequantize_group(q, scales[a0 / group], group, bits, dhat);
+            for (int64_t e = 0; e < group; ++e) {
+                store_elem(m_buf, m0 + e, dtype, load_elem(m_buf, m0 + e, dtype) + dhat[e]);
+                store_elem(out, a0 + e, dtype, load_elem(m_buf, m0 + e, dtype));
+            }
+        }
+    }
+    free(dhat); free(q);
     return 0;
 }
