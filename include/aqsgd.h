@@ -144,6 +144,30 @@ int aqsgd_seed(const aqsgd_desc* desc, const void* act, const int64_t* sample_id
                void* m_buf, void* stream);
 
 /*
+ * Algorithm 1 with its first-visit branch ("if xi not seen before": the activation is
+ * sent in full precision and m(xi) <- a(xi); otherwise the quantised change is sent).
+ * `seen` holds one byte per sample of m_buf (0 = no previous message yet); both stages
+ * keep their own copy, which stay identical because both see the same sample ids.
+ *   aqsgd_encode_seen   samples with seen == 0: m_buf[id] <- act[i], first[i] = 1, their
+ *                       slices of codes / scales are NOT written (row i of act is the
+ *                       message); other samples: exactly aqsgd_encode, first[i] = 0
+ *   aqsgd_decode_seen   samples with seen == 0: m_buf[id] <- full[i], out[i] <- full[i];
+ *                       other samples: exactly aqsgd_decode (their rows of full are not read)
+ * Both mark every sample of the call as seen afterwards.
+ *   seen    i/o  uint8[n_samples], device
+ *   first   out  int32[batch], device, 4-byte aligned
+ *   full    in   [batch, n_per] of desc.dtype, 16-byte aligned: the uncompressed rows
+ * Everything else (arguments, alignment, preconditions, status codes) as in
+ * aqsgd_encode / aqsgd_decode.  Each call enqueues three kernels on `stream`.
+ */
+int aqsgd_encode_seen(const aqsgd_desc* desc, const void* act, const int64_t* sample_ids,
+                      void* m_buf, uint8_t* seen, int32_t* first, uint8_t* codes, float* scales,
+                      void* stream);
+int aqsgd_decode_seen(const aqsgd_desc* desc, const uint8_t* codes, const float* scales,
+                      const void* full, const int64_t* sample_ids, void* m_buf, uint8_t* seen,
+                      void* out, void* stream);
+
+/*
  * Previous messages kept at low precision ("m z", Appendix H.5: z bits for the
  * previous messages; the appendix reports z = 8 and z = 2).  m(xi) is stored as z-bit
  * levels plus one binary32 scale per group, produced by the same Q with nearest

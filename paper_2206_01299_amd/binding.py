@@ -22,7 +22,8 @@ DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
-           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_lowbit_row_bytes",
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_encode_seen",
+           "aqsgd_decode_seen", "aqsgd_lowbit_row_bytes",
            "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
            "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
            "aqsgd_topk_bitmap_bytes", "aqsgd_topk_codes_bytes", "aqsgd_grad_topk_quant",
@@ -70,6 +71,10 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_grad_dequant.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_seed.restype = ctypes.c_int
         L.aqsgd_seed.argtypes = [dp, vp, vp, vp, vp]
+        L.aqsgd_encode_seen.restype = ctypes.c_int
+        L.aqsgd_encode_seen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_decode_seen.restype = ctypes.c_int
+        L.aqsgd_decode_seen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
         L.aqsgd_lowbit_row_bytes.restype = ctypes.c_size_t
         L.aqsgd_lowbit_row_bytes.argtypes = [dp, ctypes.c_int32]
         L.aqsgd_encode_lowbit.restype = ctypes.c_int
@@ -175,6 +180,20 @@ def seed(desc: Desc, act, sample_ids, m_buf, stream=None) -> None:
     """``aqsgd_seed``: uncompressed first visit, ``m_buf[sample_ids] <- act``."""
     _raise(lib().aqsgd_seed(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
                             _dev(m_buf, "m_buf"), _stream(stream)))
+
+
+def encode_seen(desc: Desc, act, sample_ids, m_buf, seen, first, codes, scales, stream=None) -> None:
+    """``aqsgd_encode_seen``: Algorithm 1's sender with the first-visit branch."""
+    _raise(lib().aqsgd_encode_seen(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
+                                   _dev(m_buf, "m_buf"), _dev(seen, "seen"), _dev(first, "first"),
+                                   _dev(codes, "codes"), _dev(scales, "scales"), _stream(stream)))
+
+
+def decode_seen(desc: Desc, codes, scales, full, sample_ids, m_buf, seen, out, stream=None) -> None:
+    """``aqsgd_decode_seen``: Algorithm 1's receiver with the first-visit branch."""
+    _raise(lib().aqsgd_decode_seen(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
+                                   _dev(full, "full"), _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"),
+                                   _dev(seen, "seen"), _dev(out, "out"), _stream(stream)))
 
 
 def lowbit_row_bytes(desc: Desc, m_bits: int) -> int:

@@ -148,12 +148,13 @@ LaunchGeom geometry(int64_t units_per_sample, int64_t units_per_block, int64_t b
 
 // Quantising side shared by aqsgd_encode and aqsgd_grad_quant.
 int run_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const void* src, const int64_t* ids,
-              void* m_buf, uint8_t* codes, float* scales, hipStream_t stream) {
+              void* m_buf, uint8_t* codes, float* scales, hipStream_t stream,
+              const uint8_t* seen = nullptr) {
     QuantArgs a;
     a.src = src; a.ids = ids; a.m_buf = m_buf; a.codes = codes; a.scales = scales;
     a.n_per = n_per; a.gps = n_per / d->group;
     a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
-    a.seed = d->rng_seed;
+    a.seed = d->rng_seed; a.seen = seen;
     hipError_t err;
     if (d->group % kChunk == 0 && a.cpg <= kMaxTeamChunks) {
         const int shape = team_shape_for(a.cpg);
@@ -167,11 +168,13 @@ int run_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const void* src
 }
 
 int run_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t* codes,
-                const float* scales, const int64_t* ids, void* m_buf, void* out, hipStream_t stream) {
+                const float* scales, const int64_t* ids, void* m_buf, void* out, hipStream_t stream,
+                const uint8_t* seen = nullptr) {
     DequantArgs a;
     a.codes = codes; a.scales = scales; a.ids = ids; a.m_buf = m_buf; a.out = out;
     a.n_per = n_per; a.gps = n_per / d->group; a.cps = n_per / kChunk;
     a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
+    a.seen = seen;
     hipError_t err;
     if (d->group % kChunk == 0) {
         const int unroll = tuning().dequant_unroll;
@@ -183,30 +186,68 @@ int run_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
-// Row copy for the uncompressed first visit: 16 bytes per lane and step, streaming.
+// Row copy for the uncompressed first visit: m_buf[ids[i]] <- act[i], and out[i] <- act[i]
+// when `out` is given.  With `seen`, only samples that have no previous message yet
+// (seen[id] == 0) are copied.  V = 16 bytes per lane and step (streaming accesses) when
+// the row size allows it, else one element.
+template <typename V>
 __global__ __launch_bounds__(kBlock)
-void seed_rows_kernel(const char* act, const int64_t* ids, char* m_buf, int64_t row_bytes, int batch) {
-    const int64_t n16 = row_bytes / 16;
+void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, V* out, const uint8_t* seen,
+                      int64_t units_per_row, int batch) {
     for (int i = blockIdx.y; i < batch; i += gridDim.y) {
-        const u32x4_t* src = reinterpret_cast<const u32x4_t*>(act + static_cast<int64_t>(i) * row_bytes);
-        u32x4_t* dst = reinterpret_cast<u32x4_t*>(m_buf + ids[i] * row_bytes);
-        for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < n16;
-             c += static_cast<int64_t>(gridDim.x) * kBlock)
-            __builtin_nontemporal_store(__builtin_nontemporal_load(src + c), dst + c);
+        const int64_t row = ids[i];
+        if (seen != nullptr && seen[row] != 0) continue;
+        const V* src = act + static_cast<int64_t>(i) * units_per_row;
+        V* dst = m_buf + row * units_per_row;
+        V* dst2 = out ? out + static_cast<int64_t>(i) * units_per_row : nullptr;
+        for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < units_per_row;
+             c += static_cast<int64_t>(gridDim.x) * kBlock) {
+            if constexpr (sizeof(V) == 16) {
+                const V v = __builtin_nontemporal_load(src + c);
+                __builtin_nontemporal_store(v, dst + c);
+                if (dst2) __builtin_nontemporal_store(v, dst2 + c);
+            } else {
+                const V v = src[c];
+                dst[c] = v;
+                if (dst2) dst2[c] = v;
+            }
+        }
     }
 }
 
-// Same for rows whose size is not a multiple of 16 bytes: element by element.
-template <typename T>
-__global__ __launch_bounds__(kBlock)
-void seed_rows_elem_kernel(const T* act, const int64_t* ids, T* m_buf, int64_t n_per, int batch) {
-    for (int i = blockIdx.y; i < batch; i += gridDim.y) {
-        const T* src = act + static_cast<int64_t>(i) * n_per;
-        T* dst = m_buf + ids[i] * n_per;
-        for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < n_per;
-             c += static_cast<int64_t>(gridDim.x) * kBlock)
-            dst[c] = src[c];
+template <typename V>
+hipError_t launch_seed_rows_as(const aqsgd_desc* d, int64_t row_bytes, const void* act, const int64_t* ids,
+                               void* m_buf, void* out, const uint8_t* seen, hipStream_t s) {
+    const int64_t units = row_bytes / static_cast<int64_t>(sizeof(V));
+    const LaunchGeom g = geometry(units, static_cast<int64_t>(kBlock) * (sizeof(V) == 16 ? 2 : 4), d->batch);
+    return launch_kernel(seed_rows_kernel<V>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
+                         static_cast<const V*>(act), ids, static_cast<V*>(m_buf), static_cast<V*>(out), seen,
+                         units, static_cast<int>(d->batch));
+}
+
+hipError_t launch_seed_rows(const aqsgd_desc* d, const void* act, const int64_t* ids, void* m_buf, void* out,
+                            const uint8_t* seen, hipStream_t s) {
+    const int64_t eb = d->dtype == AQSGD_F32 ? 4 : 2;
+    const int64_t row_bytes = d->n_per * eb;
+    if (row_bytes % 16 == 0) return launch_seed_rows_as<u32x4_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
+    if (eb == 4) return launch_seed_rows_as<uint32_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
+    return launch_seed_rows_as<uint16_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
+}
+
+// After a call with first-visit handling: note which samples were new, then mark them all.
+__global__ void mark_seen_kernel(const int64_t* ids, int batch, uint8_t* seen, int32_t* first) {
+    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < batch; i += gridDim.x * blockDim.x) {
+        const int64_t row = ids[i];
+        if (first) first[i] = seen[row] == 0;
+        seen[row] = 1;
     }
+}
+
+hipError_t launch_mark_seen(const aqsgd_desc* d, const int64_t* ids, uint8_t* seen, int32_t* first,
+                            hipStream_t s) {
+    const unsigned blocks = static_cast<unsigned>((d->batch + kBlock - 1) / kBlock);
+    return launch_kernel(mark_seen_kernel, dim3(blocks < 1024 ? blocks : 1024), dim3(kBlock), s, ids,
+                         static_cast<int>(d->batch), seen, first);
 }
 
 int lowbit_shape_for(int cpg) {
@@ -366,27 +407,42 @@ int aqsgd_seed(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, 
     if (d->batch == 0) return AQSGD_OK;
     if (!act || !sample_ids || !m_buf) return AQSGD_ERR_NULL;
     if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(sample_ids, 8)) return AQSGD_ERR_ALIGN;
-    const int64_t eb = d->dtype == AQSGD_F32 ? 4 : 2;
-    const int64_t row_bytes = d->n_per * eb;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    hipError_t err;
-    if (row_bytes % 16 == 0) {
-        err = launch_kernel(seed_rows_kernel, dim3(geometry(row_bytes / 16, kBlock * 2, d->batch).grid_x,
-                                                   geometry(row_bytes / 16, kBlock * 2, d->batch).grid_y),
-                            dim3(kBlock), s, static_cast<const char*>(act), sample_ids,
-                            static_cast<char*>(m_buf), row_bytes, static_cast<int>(d->batch));
-    } else {
-        const LaunchGeom g = geometry(d->n_per, kBlock * 4, d->batch);
-        if (eb == 4)
-            err = launch_kernel(seed_rows_elem_kernel<uint32_t>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
-                                static_cast<const uint32_t*>(act), sample_ids, static_cast<uint32_t*>(m_buf),
-                                d->n_per, static_cast<int>(d->batch));
-        else
-            err = launch_kernel(seed_rows_elem_kernel<uint16_t>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
-                                static_cast<const uint16_t*>(act), sample_ids, static_cast<uint16_t*>(m_buf),
-                                d->n_per, static_cast<int>(d->batch));
-    }
+    const hipError_t err = launch_seed_rows(d, act, sample_ids, m_buf, nullptr, nullptr,
+                                            static_cast<hipStream_t>(stream));
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+int aqsgd_encode_seen(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
+                      uint8_t* seen, int32_t* first, uint8_t* codes, float* scales, void* stream) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!act || !sample_ids || !m_buf || !seen || !first || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(sample_ids, 8) || !aligned(first, 4))
+        return AQSGD_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // the three launches read `seen` as it was before the call; only the last one writes it
+    int st = run_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales, s, seen);
+    if (st != AQSGD_OK) return st;
+    if (launch_seed_rows(d, act, sample_ids, m_buf, nullptr, seen, s) != hipSuccess) return AQSGD_ERR_LAUNCH;
+    return launch_mark_seen(d, sample_ids, seen, first, s) == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+int aqsgd_decode_seen(const aqsgd_desc* d, const uint8_t* codes, const float* scales, const void* full,
+                      const int64_t* sample_ids, void* m_buf, uint8_t* seen, void* out, void* stream) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK) return rc;
+    if (d->batch == 0) return AQSGD_OK;
+    if (!codes || !scales || !full || !sample_ids || !m_buf || !seen || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(sample_ids, 8) || !aligned(full, 16))
+        return AQSGD_ERR_ALIGN;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    int st = run_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out, s, seen);
+    if (st != AQSGD_OK) return st;
+    if (launch_seed_rows(d, full, sample_ids, m_buf, out, seen, s) != hipSuccess) return AQSGD_ERR_LAUNCH;
+    return launch_mark_seen(d, sample_ids, seen, nullptr, s) == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
 size_t aqsgd_lowbit_row_bytes(const aqsgd_desc* d, int32_t m_bits) {

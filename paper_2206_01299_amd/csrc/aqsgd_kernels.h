@@ -43,6 +43,7 @@ struct QuantArgs {
     int32_t group;             // G
     int32_t cpg;               // chunks per group (G / 8), team kernels only
     uint64_t seed;
+    const uint8_t* seen;       // or nullptr; else samples with seen[id] == 0 are skipped
 };
 
 struct DequantArgs {
@@ -57,6 +58,7 @@ struct DequantArgs {
     int32_t batch;
     int32_t group;
     int32_t cpg;
+    const uint8_t* seen;       // or nullptr; else samples with seen[id] == 0 are skipped
 };
 
 constexpr int kBlock = 256;
@@ -165,6 +167,7 @@ __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_
 
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;      // flat offset of sample i
         const char* src_s = static_cast<const char*>(a.src) + src0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
@@ -206,6 +209,7 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
     const uint32_t cps = static_cast<uint32_t>(a.cps);
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         char* out_s = static_cast<char*>(a.out) + out0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
@@ -285,6 +289,7 @@ void quant_anyshape_kernel(const QuantArgs a, const int bits, const int rounding
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
         for (int64_t gs = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; gs < a.gps;
@@ -344,6 +349,7 @@ void dequant_anyshape_kernel(const DequantArgs a, const int bits) {
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
         for (int64_t gs = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; gs < a.gps;
