@@ -97,6 +97,16 @@ def test_long_samples_cross_block_strides(H):
     H.replay_and_compare(cfg, calls_per_epoch=2, epochs=2, log=lambda *a, **k: None)
 
 
+def test_more_samples_in_a_call_than_grid_rows(H):
+    """70001 samples in one call: the launch has at most 65535 rows of workgroups, so
+    the kernels' loop over samples must come round a second time."""
+    quiet = lambda *a, **k: None
+    cfg = _case_cfg("f16", 4, 64, W.NEAREST, groups_per_sample=2, batch=70001, n_samples=70010)
+    H.replay_and_compare(cfg, calls_per_epoch=1, epochs=2, log=quiet)
+    cfg = _case_cfg("f32", 8, 12, W.STOCHASTIC, groups_per_sample=1, batch=66000, n_samples=66000)   # any-shape kernels
+    H.replay_and_compare(cfg, calls_per_epoch=1, epochs=2, log=quiet)
+
+
 # ---------------------------------------------------------------------------
 # edge cases
 # ---------------------------------------------------------------------------
