@@ -235,7 +235,9 @@ int aqsgd_grad_topk_dequant(const aqsgd_desc* desc, int32_t keep, const uint8_t*
  *
  *   create    fills dev_row_ids with 0 .. slots*batch-1 (synchronously) and creates events
  *   prefetch  window <- host rows of host_ids (HOST int64[batch], distinct), on copy_stream;
- *             a window must be released before it is prefetched again
+ *             a window must be released before it is prefetched again, and a sample that
+ *             sits in an unreleased window cannot be prefetched (its newest row is in that
+ *             window, not in host memory): both are refused with AQSGD_ERR_SHAPE
  *   acquire   makes compute_stream wait for the window's rows; returns the sample_ids
  *             pointer (device, batch entries) to pass to the codec with m_buf = dev_rows,
  *             n_samples = slots*batch

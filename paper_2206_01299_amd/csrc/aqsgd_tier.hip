@@ -59,6 +59,12 @@ int aqsgd_tier_prefetch(aqsgd_tier* t, int32_t slot, const int64_t* host_ids, vo
     for (int i = 0; i < t->batch; ++i) {
         if (host_ids[i] < 0 || host_ids[i] >= t->n_samples) return AQSGD_ERR_SHAPE;
         if (t->held[static_cast<size_t>(slot) * t->batch + i] != -1) return AQSGD_ERR_SHAPE;   // not released
+        // a sample that sits in a window (this call's or an unreleased one) has a newer row
+        // there than in host memory: loading it again would fork it
+        for (int64_t h : t->held)
+            if (h == host_ids[i]) return AQSGD_ERR_SHAPE;
+        for (int j = 0; j < i; ++j)
+            if (host_ids[j] == host_ids[i]) return AQSGD_ERR_SHAPE;
     }
     hipStream_t cs = static_cast<hipStream_t>(copy_stream);
     for (int i = 0; i < t->batch; ++i) {
