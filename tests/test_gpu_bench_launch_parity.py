@@ -1,0 +1,59 @@
+"""Parity in the launch configuration that bench.py times: the GPT2-1.5B-shaped
+boundary at full size (8192-sample buffers, float16 [4, 1024, 1600] micro-batches),
+steps recorded into a HIP graph with the forward pairs dealt over two streams and the
+backward pairs over two more, replayed twice.  Every output of every step, and every
+visited row of both copies of m, must equal the oracle's after each replay."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+from paper_2206_01299_amd import binding as B
+from paper_2206_01299_amd import workloads as W
+
+
+def test_graph_on_four_streams_at_full_size_matches_the_oracle():
+    if not torch.cuda.is_available():
+        pytest.fail("needs the MI355X")
+    B.lib()
+    import bench
+    import gpu_harness as H
+    cfg = W.gpt2_4bit()
+    steps = 8
+    wl = bench.Workload(cfg, pool=steps)                 # m starts at zero: replay 1 = first visits
+    wl.make_streams(4)
+    main = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=main):           # the enqueue pattern of bench.timed_steps
+        fork = torch.cuda.Event()
+        fork.record(main)
+        for st in wl.streams:
+            st.wait_event(fork)
+        for k in range(steps):
+            wl.step_on_streams(k)
+        for st in wl.streams:
+            done = torch.cuda.Event()
+            done.record(st)
+            main.wait_event(done)
+    torch.cuda.synchronize()
+    assert not bool(wl.m_send[wl.ids[0]].any())          # capture ran nothing
+
+    ids = wl.ids[:steps].cpu().numpy()
+    acts = [W.from_torch(wl.act[k], cfg.dtype).reshape(cfg.batch, cfg.n_per) for k in range(steps)]
+    grads = [W.from_torch(wl.grad[k], cfg.dtype).reshape(cfg.batch, cfg.n_per) for k in range(steps)]
+    cpu = H.OracleBoundary(cfg, ids.reshape(-1))
+    for replay in range(2):
+        graph.replay()
+        torch.cuda.synchronize()
+        for k in range(steps):
+            want = cpu.forward(acts[k], ids[k], 0)
+            H.compare_call(f"replay {replay} step {k} fwd", cfg, (wl.codes[k], wl.scales[k], wl.out[k]), want)
+            wantb = cpu.backward(grads[k], 0)
+            H.compare_call(f"replay {replay} step {k} bwd", cfg, (wl.bcodes[k], wl.bscales[k], wl.gout[k]), wantb)
+        order = torch.from_numpy(cpu.order).to(wl.dev)
+        for name, dev_m, want_m in (("send", wl.m_send, cpu.m_send), ("recv", wl.m_recv, cpu.m_recv)):
+            got = W.from_torch(dev_m[order], cfg.dtype).reshape(len(cpu.order), cfg.n_per)
+            assert H.same_bytes(got, want_m), f"replay {replay} m_{name}: {H.first_diff(got, want_m)}"
+        if replay == 0:
+            assert bool(wl.scales[0].any())
