@@ -87,8 +87,8 @@ size_t aqsgd_codes_bytes(const aqsgd_desc* desc);
 size_t aqsgd_scales_count(const aqsgd_desc* desc);
 
 /*
- * Sender side of the forward message (Algorithm 2, "on network a"; Algorithm 1's
- * update of m).  For each sample i of the call, with row = sample_ids[i]:
+ * Sender side of the forward message (Algorithm 2, the block for network a;
+ * Algorithm 1's update of m).  For each sample i of the call, with row = sample_ids[i]:
  *     delta = act[i] - m_buf[row]                     (binary32)
  *     codes, scales <- Q(delta)                       (Section 4.1)
  *     m_buf[row] <- dtype(m_buf[row] + Q(delta))      (in place)
@@ -104,7 +104,7 @@ int aqsgd_encode(const aqsgd_desc* desc, const void* act, const int64_t* sample_
                  void* m_buf, uint8_t* codes, float* scales, void* stream);
 
 /*
- * Receiver side (Algorithm 2, "on network b"): applies the same update to the
+ * Receiver side (Algorithm 2, the block for network b): applies the same update to the
  * receiver's copy of m and hands m(xi) on as the activation of the next stage.
  *     m_buf[row] <- dtype(m_buf[row] + Q^-1(codes, scales));  out[i] <- m_buf[row]
  * After matching encode/decode calls the two copies of m_buf are bit-identical.
@@ -116,8 +116,8 @@ int aqsgd_decode(const aqsgd_desc* desc, const uint8_t* codes, const float* scal
                  const int64_t* sample_ids, void* m_buf, void* out, void* stream);
 
 /*
- * Backward message (Algorithm 1: "Machine b sends Q(gradient)"): direct
- * quantisation of the activation-gradient, no buffer.
+ * Backward message (Algorithm 1, the step in which machine b returns the quantised
+ * gradient): direct quantisation of the activation-gradient, no buffer.
  *   grad  in  [batch, n_per];  codes, scales out as above.
  */
 int aqsgd_grad_quant(const aqsgd_desc* desc, const void* grad, uint8_t* codes,
@@ -128,9 +128,9 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
                        void* out, void* stream);
 
 /*
- * Uncompressed first visit (Algorithm 1: "if xi not seen before: set m(xi) = a(xi)";
- * Appendix D runs a whole warm-up epoch this way): the message is the activation
- * itself, at full precision, and both stages store it as m(xi).
+ * Uncompressed first visit (Algorithm 1's branch for a sample without a previous
+ * message; Appendix D runs a whole warm-up epoch this way): the message is the
+ * activation itself, at full precision, and both stages store it as m(xi).
  *     m_buf[sample_ids[i]] <- act[i]        for every sample i of the call
  * The sender calls it with its activation, the receiver with the activation it
  * received, which keeps the two copies identical.  A later aqsgd_encode of the same
@@ -144,8 +144,9 @@ int aqsgd_seed(const aqsgd_desc* desc, const void* act, const int64_t* sample_id
                void* m_buf, void* stream);
 
 /*
- * Algorithm 1 with its first-visit branch ("if xi not seen before": the activation is
- * sent in full precision and m(xi) <- a(xi); otherwise the quantised change is sent).
+ * Algorithm 1 with its first-visit branch (a sample without a previous message: the
+ * activation is sent in full precision and m(xi) <- a(xi); otherwise the quantised
+ * change is sent).
  * `seen` holds one byte per sample of m_buf (0 = no previous message yet); both stages
  * keep their own copy, which stay identical because both see the same sample ids.
  *   aqsgd_encode_seen   samples with seen == 0: m_buf[id] <- act[i], first[i] = 1, their
@@ -219,10 +220,10 @@ int aqsgd_grad_topk_dequant(const aqsgd_desc* desc, int32_t keep, const uint8_t*
                             const uint8_t* codes, const float* scales, void* out, void* stream);
 
 /*
- * Host-memory tier for the previous messages (Section 3.3, "System Implementations
- * and Optimizations": m(xi) is kept in a local buffer in host memory, loaded to the
- * GPU before the forward pass of its sample and written back after the update, both
- * hidden behind the computation of other samples; Appendix G).
+ * Host-memory tier for the previous messages (the implementation notes of Section 3.3
+ * and Appendix G: m(xi) lives in host memory, is brought to the GPU before the forward
+ * pass of its sample and goes back after the update, both behind the computation of
+ * other samples).
  *
  * All N rows live in PINNED HOST memory; HBM holds `slots` windows of `batch` rows.
  * A micro-batch's rows are copied into a window ahead of time on a copy stream

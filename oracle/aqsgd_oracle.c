@@ -7,17 +7,17 @@
  * tests, the smoke check and the CPU-baseline leg of the benchmark use it.
  *
  * What it computes
- *   - Sender and receiver sides of the forward message (Algorithm 2, "on
- *     network a" / "on network b"; Algorithm 1's update of m):
+ *   - Sender and receiver sides of the forward message (Algorithm 2, the
+ *     blocks for network a and for network b; Algorithm 1's update of m):
  *         delta   = a(xi) - m(xi)
  *         Delta m = Q(delta)
  *         m(xi)  <- m(xi) + Delta m          (identically on both machines)
  *   - The backward message Q(grad) and its reconstruction (Algorithm 1,
- *     the two comment lines about Machine b sending Q(grad)).
- *   - Q itself: Section 4.1 ("normalizes a given vector into [-1,1] and
- *     quantize each number into a b-bit integer by uniformly partitioning
- *     [-1,1]"), with stochastic rounding as an option because Theorem 3.1
- *     asks for an unbiased Q (its footnote rounds "stochastically").
+ *     the two comment lines in which machine b returns Q(grad)).
+ *   - Q itself (Section 4.1): a vector is scaled into [-1, 1] and each entry
+ *     becomes a b-bit integer on a uniform partition of that interval; with
+ *     stochastic rounding as an option because Theorem 3.1 asks for an
+ *     unbiased Q (the example in its footnote rounds at random).
  *
  * Readings taken where the paper leaves room (each is also listed in the
  * design notes of this repository):
@@ -320,9 +320,10 @@ int aqsgd_oracle_encode(int dtype, int bits, int64_t group, int rounding, uint64
 }
 
 /* ------------------------------------------------------------------ */
-/* Uncompressed first visit (Algorithm 1: "if xi not seen before, set  */
-/* m(xi) = a(xi)"; Appendix D's warm-up epoch): the row is the          */
-/* activation, bit for bit, on whichever machine calls it.              */
+/* Uncompressed first visit (Algorithm 1's branch for a sample without  */
+/* a previous message, which sets m(xi) to a(xi); Appendix D's warm-up   */
+/* epoch): the row is the activation, bit for bit, on whichever machine  */
+/* calls it.                                                            */
 /* ------------------------------------------------------------------ */
 int aqsgd_oracle_seed(int dtype, int64_t batch, int64_t n_per, const void* act,
                       const int64_t* ids, void* m_buf)
@@ -425,9 +426,9 @@ int aqsgd_oracle_grad_dequant(int dtype, int bits, int64_t group, int64_t batch,
 }
 
 /* ------------------------------------------------------------------ */
-/* Previous messages kept at low precision ("m z", Appendix H.5: "we    */
-/* perform quantization on m, where mz means that we use z bits for     */
-/* previous messages").  The appendix says no more than that; reading:  */
+/* Previous messages kept at low precision (the "m z" runs of Appendix   */
+/* H.5, in which m itself is quantised to z bits).  The appendix says    */
+/* no more than that; reading:                                           */
 /*   - m(xi) is stored as z-bit levels plus one binary32 max-abs scale   */
 /*     per group (the message's group size), through the same Q with     */
 /*     nearest rounding, so that both machines store the same bits;      */
@@ -540,9 +541,9 @@ int aqsgd_oracle_decode_lowbit(int dtype, int bits, int m_bits, int64_t group, i
 }
 
 /* ------------------------------------------------------------------ */
-/* Sparsified backward message ("bw8[0.2]", Appendix H.6: "we keep only */
-/* the top 20% gradients and then perform 8-bit quantization").         */
-/* The appendix says no more; reading: per group of G elements the      */
+/* Sparsified backward message (the "bw8[0.2]" runs of Appendix H.6: the */
+/* largest fifth of the gradient entries is kept, then quantised to      */
+/* 8 bits).  The appendix says no more; reading: per group of G elements the */
 /* `keep` entries of largest magnitude survive (equal magnitudes: the    */
 /* lower index first); survivors are quantised by Q_b with the group's   */
 /* max-abs scale (the largest entry always survives), everything else   */
@@ -634,9 +635,9 @@ int aqsgd_oracle_grad_topk_dequant(int dtype, int bits, int64_t group, int64_t k
 }
 
 /* ------------------------------------------------------------------ */
-/* Algorithm 1 with its first-visit branch ("if xi not seen before":   */
-/* the activation travels uncompressed and m(xi) <- a(xi); otherwise   */
-/* the change is quantised).  seen[id] != 0 marks samples that have a   */
+/* Algorithm 1 with its first-visit branch (a sample without a previous  */
+/* message: the activation travels uncompressed and m(xi) <- a(xi);     */
+/* otherwise the change is quantised).  seen[id] != 0 marks samples that have a   */
 /* previous message.  Sender: first[i] = 1 tells the caller that row i  */
 /* of act is the message of sample i and that the sample's slices of    */
 /* codes / scales were not written.  Receiver: `full` holds those rows  */

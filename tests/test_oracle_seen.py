@@ -4,7 +4,7 @@ quantised change.
 
 Fixed independently of the code under test:
   * a first visit reproduces the activation bit for bit on both machines (the
-    algorithm's "send a(xi) in full precision; m(xi) <- a(xi)");
+    algorithm sends it in full precision and both set m(xi) to it);
   * a second visit with an unchanged activation sends nothing (scale 0, codes 0);
   * a seen sample's slices are what the plain, separately pinned encoder gives for
     the same call (same flat indices, same random offsets);
