@@ -472,4 +472,90 @@ __device__ __forceinline__ uint64_t load_codes_at(const uint8_t* p) {
     }
 }
 
+// ---------------------------------------------------------------------------
+// float32 in 16-byte units.
+//
+// A float32 chunk is 32 bytes; taken as one piece per lane, each of its two
+// 16-byte accesses touches every cache line of the wavefront's span and uses half
+// of it.  Instead a lane's eight elements are two *units* of four that lie a team
+// width apart, so that consecutive lanes access consecutive 16 bytes, as the
+// 16-bit types do (measured on the float32 stress shape with encode's traffic:
+// 6.3 instead of 5.2 TB/s).  Four b-bit codes are b/2 bytes, whole bytes for every
+// width but 3, which keeps the one-piece layout.
+// ---------------------------------------------------------------------------
+constexpr int kUnit = 4;           // elements of a 16-byte float32 unit
+
+template <int DT, int BITS> struct UnitLayout {
+    static constexpr bool value = DT == AQSGD_F32 && BITS != 3;
+};
+
+__device__ __forceinline__ Raw<AQSGD_F32> load_raw_units(const char* pa, const char* pb) {
+    Raw<AQSGD_F32> r;
+    r.lo = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(pa));
+    r.hi = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t*>(pb));
+    return r;
+}
+
+__device__ __forceinline__ void store_raw_units(char* pa, char* pb, const Raw<AQSGD_F32>& r) {
+    __builtin_nontemporal_store(r.lo, reinterpret_cast<f32x4_t*>(pa));
+    __builtin_nontemporal_store(r.hi, reinterpret_cast<f32x4_t*>(pb));
+}
+
+// The two halves of pack_levels' word: levels 0..3 and 4..7, 4*BITS bits each.
+template <int BITS>
+__device__ __forceinline__ uint32_t low_unit_codes(uint64_t w) {
+    return static_cast<uint32_t>(w) & static_cast<uint32_t>((uint64_t{1} << (4 * BITS)) - 1);
+}
+template <int BITS>
+__device__ __forceinline__ uint32_t high_unit_codes(uint64_t w) {
+    return static_cast<uint32_t>(w >> (4 * BITS));
+}
+
+// Codes of one unit to / from the byte stream; unit u of the call starts at byte
+// u * BITS / 2.
+template <int BITS>
+__device__ __forceinline__ void store_unit_codes(uint8_t* p, uint32_t w) {
+    static_assert(BITS == 2 || BITS == 4 || BITS == 6 || BITS == 8, "whole bytes per unit");
+    if constexpr (BITS == 8) {
+        *reinterpret_cast<uint32_t*>(p) = w;
+    } else if constexpr (BITS == 4) {
+        *reinterpret_cast<uint16_t*>(p) = static_cast<uint16_t>(w);
+    } else if constexpr (BITS == 2) {
+        p[0] = static_cast<uint8_t>(w);
+    } else {                                         // 3 bytes, no alignment to rely on
+        p[0] = static_cast<uint8_t>(w);
+        p[1] = static_cast<uint8_t>(w >> 8);
+        p[2] = static_cast<uint8_t>(w >> 16);
+    }
+}
+
+template <int BITS>
+__device__ __forceinline__ uint32_t load_unit_codes(const uint8_t* p) {
+    static_assert(BITS == 2 || BITS == 4 || BITS == 6 || BITS == 8, "whole bytes per unit");
+    if constexpr (BITS == 8) {
+        return *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (BITS == 4) {
+        return *reinterpret_cast<const uint16_t*>(p);
+    } else if constexpr (BITS == 2) {
+        return p[0];
+    } else {
+        return static_cast<uint32_t>(p[0]) | (static_cast<uint32_t>(p[1]) << 8) |
+               (static_cast<uint32_t>(p[2]) << 16);
+    }
+}
+
+// Rounding offsets of two units whose first elements have flat indices ja and jb
+// (multiples of 4): one Philox block each.
+__device__ __forceinline__ void units_uniforms(uint64_t seed, uint64_t ja, uint64_t jb, float (&r)[kChunk]) {
+    const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
+    const uint64_t blka = ja >> 2, blkb = jb >> 2;
+    uint32_t w[4];
+    philox4x32_10(static_cast<uint32_t>(blka), static_cast<uint32_t>(blka >> 32), k0, k1, w);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = uniform_from_word(w[e]);
+    philox4x32_10(static_cast<uint32_t>(blkb), static_cast<uint32_t>(blkb >> 32), k0, k1, w);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[4 + e] = uniform_from_word(w[e]);
+}
+
 }  // namespace aqsgd

@@ -77,20 +77,30 @@ template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
 __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char* src_s, char* m_s,
                                                  uint8_t* codes_s, float* scales_s, int64_t src0,
                                                  int64_t g, const uint32_t (&cc)[CPL],
+                                                 const uint32_t (&ua)[CPL], const uint32_t (&ub)[CPL],
                                                  int lane_in_team, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
     constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
+    constexpr int kUnitBytes = kUnit * kEB;
+    constexpr bool kUnits = UnitLayout<DT, BITS>::value;   // float32: a chunk is two separate 16-byte units
 
     // ---- issue every load of the group ------------------------------------------
     const int64_t goff = g * a.group;                    // element offset within the sample
     Raw<DT> ra[CPL], rm[CPL];
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        ra[k] = load_raw_at<DT>(src_s + goff * kEB + cc[k] * kChunkBytes);
-        if constexpr (HAS_BUF) rm[k] = load_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes);
-        else rm[k] = zero_raw<DT>();
+        if constexpr (kUnits) {
+            ra[k] = load_raw_units(src_s + goff * kEB + ua[k] * kUnitBytes, src_s + goff * kEB + ub[k] * kUnitBytes);
+            if constexpr (HAS_BUF)
+                rm[k] = load_raw_units(m_s + goff * kEB + ua[k] * kUnitBytes, m_s + goff * kEB + ub[k] * kUnitBytes);
+            else rm[k] = zero_raw<DT>();
+        } else {
+            ra[k] = load_raw_at<DT>(src_s + goff * kEB + cc[k] * kChunkBytes);
+            if constexpr (HAS_BUF) rm[k] = load_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes);
+            else rm[k] = zero_raw<DT>();
+        }
     }
     // Keep all of the group's loads ahead of the first use: the scheduler would
     // otherwise sink them next to their consumers and leave two or three in flight.
@@ -120,7 +130,11 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
     for (int k = 0; k < CPL; ++k) {
         float r[kChunk];
         if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
-            chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
+            if constexpr (kUnits)
+                units_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + ua[k] * kUnit,
+                               static_cast<uint64_t>(src0 + goff) + ub[k] * kUnit, r);
+            else
+                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
         } else {
 #pragma unroll
             for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
@@ -132,6 +146,15 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
             dh[e] = value_of(q[e], sc);
         }
         uint8_t* group_codes = codes_s + goff / kChunk * BITS;
+        if constexpr (kUnits) {
+            const uint64_t w = pack_levels<BITS>(q);
+            store_unit_codes<BITS>(group_codes + ua[k] * (BITS / 2), low_unit_codes<BITS>(w));
+            store_unit_codes<BITS>(group_codes + ub[k] * (BITS / 2), high_unit_codes<BITS>(w));
+            if constexpr (HAS_BUF)
+                store_raw_units(m_s + goff * kEB + ua[k] * kUnitBytes, m_s + goff * kEB + ub[k] * kUnitBytes,
+                                updated_chunk<DT>(rm[k], dh));
+            continue;
+        }
         if (BITS == 3 && TEAM % 4 == 0 && a.cpg % 4 == 0) {
             // whole quads of lanes are inside the group or past its end
             const bool inside = k * TEAM + lane_in_team < a.cpg;
@@ -164,6 +187,15 @@ __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_
 #pragma unroll
     for (int k = 0; k < CPL; ++k)
         cc[k] = static_cast<uint32_t>(min(k * TEAM + lane_in_team, a.cpg - 1));
+    // The same ownership in 16-byte units for the float32 layout: row k of the team
+    // covers units [2k TEAM, 2(k+1) TEAM), a lane takes one from each half of the row;
+    // past the group's end a lane repeats the last unit (same values, same stores).
+    uint32_t ua[CPL], ub[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        ua[k] = static_cast<uint32_t>(min(2 * k * TEAM + lane_in_team, 2 * a.cpg - 1));
+        ub[k] = static_cast<uint32_t>(min((2 * k + 1) * TEAM + lane_in_team, 2 * a.cpg - 1));
+    }
 
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
@@ -179,7 +211,8 @@ __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_
             const int64_t g = gbase + team;              // uniform over the team
             if (g < a.gps)
                 quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF>(a, src_s, m_s, codes_s, scales_s,
-                                                                      src0, g, cc, lane_in_team, wave_max);
+                                                                      src0, g, cc, ua, ub, lane_in_team,
+                                                                      wave_max);
         }
     }
 }
@@ -269,9 +302,90 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
     }
 }
 
+// The same for float32 in 16-byte units (see UnitLayout): one unit of four elements
+// per lane and access, UNITS of them per step, so consecutive lanes touch
+// consecutive 16 bytes of m, out and, b/2 bytes each, of the codes.
+constexpr int64_t kMaxUnitChunks = int64_t{1} << 30;     // unit indices of a sample fit 32 bits
+
+template <int BITS, int UNITS, bool HAS_BUF>
+__device__ __forceinline__ void dequant_units_body(const DequantArgs& a) {
+    constexpr int kUnitBytes = kUnit * 4;
+    constexpr uint32_t kStep = kBlock * UNITS;
+    const uint32_t upg = 2u * static_cast<uint32_t>(a.cpg);              // units per group
+    const float rcp_upg = 1.0f / static_cast<float>(upg);
+    const uint32_t ups = 2u * static_cast<uint32_t>(a.cps);              // units per sample
+    for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
+        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
+        const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
+        char* out_s = static_cast<char*>(a.out) + out0 * 4;
+        char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * 4 : nullptr;
+        const uint8_t* codes_s = a.codes + out0 / kChunk * BITS;
+        const float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
+
+        for (uint32_t ubase = blockIdx.x * kStep; ubase < ups; ubase += gridDim.x * kStep) {
+            const uint32_t g0 = ubase / upg;
+            const uint32_t r0 = ubase - g0 * upg;
+            uint32_t w[UNITS];
+            float scale[UNITS];
+            f32x4_t rm[UNITS];
+            uint32_t us[UNITS];
+            bool ok[UNITS];
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const uint32_t unit = ubase + u * kBlock + threadIdx.x;    // unit within the sample
+                ok[u] = unit < ups;
+                us[u] = ok[u] ? unit : ups - 1;
+                const uint32_t x = r0 + (us[u] - ubase);                   // < upg + kStep
+                uint32_t dg;
+                if (upg >= kStep) {
+                    dg = x >= upg ? 1u : 0u;
+                } else {                                                   // x < 2^23: float is exact enough
+                    dg = static_cast<uint32_t>(static_cast<float>(x) * rcp_upg);
+                    if (dg * upg > x) --dg;
+                    else if ((dg + 1) * upg <= x) ++dg;
+                }
+                w[u] = load_unit_codes<BITS>(codes_s + static_cast<uint64_t>(us[u]) * (BITS / 2));
+                scale[u] = scales_s[g0 + dg];
+                if constexpr (HAS_BUF)
+                    rm[u] = __builtin_nontemporal_load(
+                        reinterpret_cast<const f32x4_t*>(m_s + static_cast<uint64_t>(us[u]) * kUnitBytes));
+            }
+            __builtin_amdgcn_sched_barrier(0);           // every load is out before the first use
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) {
+                const GroupScale sc = scale_from_wire<BITS>(scale[u]);
+                float q[kChunk];
+                unpack_levels<BITS>(w[u], q);            // the unit's four levels are the word's first four
+                f32x4_t v;
+#pragma unroll
+                for (int e = 0; e < kUnit; ++e) {
+                    const float dh = value_of(q[e], sc);
+                    if constexpr (HAS_BUF) v[e] = rm[u][e] + dh;
+                    else v[e] = dh;
+                }
+                if (ok[u]) {
+                    if constexpr (HAS_BUF)
+                        __builtin_nontemporal_store(
+                            v, reinterpret_cast<f32x4_t*>(m_s + static_cast<uint64_t>(us[u]) * kUnitBytes));
+                    __builtin_nontemporal_store(
+                        v, reinterpret_cast<f32x4_t*>(out_s + static_cast<uint64_t>(us[u]) * kUnitBytes));
+                }
+            }
+        }
+    }
+}
+
 template <int DT, int BITS, int UNROLL>
 __global__ __launch_bounds__(kBlock)
 void dequant_flat_kernel(const DequantArgs a) {
+    if constexpr (UnitLayout<DT, BITS>::value) {
+        if (a.cps <= kMaxUnitChunks) {                   // else the unit index would pass 32 bits
+            if (a.m_buf) dequant_units_body<BITS, 2 * UNROLL, true>(a);
+            else dequant_units_body<BITS, 2 * UNROLL, false>(a);
+            return;
+        }
+    }
     if (a.m_buf) dequant_flat_body<DT, BITS, UNROLL, true>(a);
     else dequant_flat_body<DT, BITS, UNROLL, false>(a);
 }
