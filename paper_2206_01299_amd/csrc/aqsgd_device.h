@@ -3,7 +3,9 @@
 // Work is organised in "chunks" of 8 consecutive elements: 16 bytes of
 // float16/bfloat16 (one 128-bit access per lane, fully coalesced across a
 // wavefront) or 32 bytes of float32.  Eight b-bit codes are b whole bytes, so a
-// lane's codes never share a byte with a neighbour's.
+// lane's codes never share a byte with a neighbour's.  The main kernels hold a
+// float32 lane's eight elements as two separate 16-byte units instead (end of
+// this file), which gives float32 the same access shape as the 16-bit types.
 //
 // All arithmetic is binary32 with one rounding per operation (the translation
 // unit is compiled with floating-point contraction off); the order of the
