@@ -267,6 +267,17 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
                     int32_t* flag, void* stream);
 
 /*
+ * Tuning helper: how launches are cut into workgroups, for the whole process.  It never
+ * changes a result bit.  max_blocks bounds the workgroups of one launch (kernels loop
+ * when it is smaller than the work), dequant_unroll (1, 2 or 4) is the number of chunks a
+ * lane of the dequantising kernel takes per step; 0 restores the value from the
+ * environment (AQSGD_MAX_BLOCKS, AQSGD_DEQUANT_UNROLL) or the built-in default.  Not to
+ * be called while another host thread is inside a codec call.  AQSGD_ERR_SHAPE for values
+ * out of range.
+ */
+int aqsgd_set_launch_shape(int64_t max_blocks, int32_t dequant_unroll);
+
+/*
  * Measurement helper: the next codec launch made by the calling host thread
  * stamps `start_event` and `stop_event` (hipEvent_t created with timing enabled,
  * passed as void*; either may be NULL) with the kernel's own begin and end, so

@@ -27,7 +27,7 @@ EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_dec
            "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
            "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
            "aqsgd_topk_bitmap_bytes", "aqsgd_topk_codes_bytes", "aqsgd_grad_topk_quant",
-           "aqsgd_grad_topk_dequant", "aqsgd_check_ids",
+           "aqsgd_grad_topk_dequant", "aqsgd_check_ids", "aqsgd_set_launch_shape",
            "aqsgd_profile_next_launch", "aqsgd_strerror", "aqsgd_version")
 
 
@@ -104,6 +104,8 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_tier_destroy.argtypes = [vp]
         L.aqsgd_check_ids.restype = ctypes.c_int
         L.aqsgd_check_ids.argtypes = [vp, ctypes.c_int64, ctypes.c_int64, vp, vp]
+        L.aqsgd_set_launch_shape.restype = ctypes.c_int
+        L.aqsgd_set_launch_shape.argtypes = [ctypes.c_int64, ctypes.c_int32]
         L.aqsgd_profile_next_launch.restype = ctypes.c_int
         L.aqsgd_profile_next_launch.argtypes = [vp, vp]
         L.aqsgd_strerror.restype = ctypes.c_char_p
@@ -242,6 +244,12 @@ def grad_topk_dequant(desc: Desc, keep: int, bitmap, codes, scales, out, stream=
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:
     _raise(lib().aqsgd_check_ids(_dev(sample_ids, "sample_ids"), sample_ids.numel(), n_samples,
                                  _dev(flag, "flag"), _stream(stream)))
+
+
+def set_launch_shape(max_blocks: int = 0, dequant_unroll: int = 0) -> None:
+    """``aqsgd_set_launch_shape``: bound the workgroups per launch / pick the dequantising
+    kernel's unroll for this process; 0 restores the environment's or the built-in value."""
+    _raise(lib().aqsgd_set_launch_shape(max_blocks, dequant_unroll))
 
 
 def profile_next_launch(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> None:

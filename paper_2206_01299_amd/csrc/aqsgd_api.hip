@@ -62,7 +62,8 @@ hipError_t launch_lowbit(int dtype, int bits, int m_bits, int shape, bool sender
 namespace {
 
 // Launch-shape knobs.  They change how the work is cut into workgroups, never a
-// result bit.  Read once from the environment so a sweep needs no rebuild.
+// result bit.  Defaults come from the environment, once, so a sweep needs no
+// rebuild; aqsgd_set_launch_shape overrides them for the process.
 struct Tuning {
     int64_t max_blocks;      // upper bound on workgroups per launch
     int dequant_unroll;      // chunks per lane and step in the dequantising kernel (1, 2, 4)
@@ -76,14 +77,16 @@ int env_int(const char* name, int fallback) {
     return (end && *end == '\0' && x > 0 && x < (1L << 30)) ? static_cast<int>(x) : fallback;
 }
 
-const Tuning& tuning() {
-    static const Tuning t = [] {
-        Tuning x;
-        x.max_blocks = env_int("AQSGD_MAX_BLOCKS", 1 << 20);
-        const int u = env_int("AQSGD_DEQUANT_UNROLL", 2);
-        x.dequant_unroll = (u == 1 || u == 2 || u == 4) ? u : 2;
-        return x;
-    }();
+Tuning tuning_from_env() {
+    Tuning x;
+    x.max_blocks = env_int("AQSGD_MAX_BLOCKS", 1 << 20);
+    const int u = env_int("AQSGD_DEQUANT_UNROLL", 2);
+    x.dequant_unroll = (u == 1 || u == 2 || u == 4) ? u : 2;
+    return x;
+}
+
+Tuning& tuning() {
+    static Tuning t = tuning_from_env();
     return t;
 }
 
@@ -520,6 +523,16 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
     hipLaunchKernelGGL(check_ids_kernel, dim3(static_cast<unsigned>(blocks < 1024 ? blocks : 1024)),
                        dim3(kBlock), 0, static_cast<hipStream_t>(stream), sample_ids, batch, n_samples, flag);
     return hipGetLastError() == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+}
+
+int aqsgd_set_launch_shape(int64_t max_blocks, int32_t dequant_unroll) {
+    if (max_blocks < 0 || max_blocks >= (int64_t{1} << 30)) return AQSGD_ERR_SHAPE;
+    if (dequant_unroll != 0 && dequant_unroll != 1 && dequant_unroll != 2 && dequant_unroll != 4)
+        return AQSGD_ERR_SHAPE;
+    const Tuning env = tuning_from_env();
+    tuning().max_blocks = max_blocks ? max_blocks : env.max_blocks;
+    tuning().dequant_unroll = dequant_unroll ? dequant_unroll : env.dequant_unroll;
+    return AQSGD_OK;
 }
 
 int aqsgd_profile_next_launch(void* start_event, void* stop_event) {
