@@ -231,19 +231,29 @@ __device__ __forceinline__ float uniform_from_word(uint32_t w) {
     return static_cast<float>(w >> 8) * 0x1p-24f;      // 24 bits: exact in binary32
 }
 
-// Rounding offsets of one chunk whose first element has flat index j0 (a
-// multiple of 8): block j0/4 feeds elements 0..3, block j0/4 + 1 elements 4..7.
+// The vector kernels carry a rounding offset r as r * 2^32, which for the uniform
+// draw is the Philox word with its low byte cleared (24 significant bits: exact in
+// binary32) and for nearest rounding 2^31.  level_of() adds it to t with one fused
+// multiply-add, RN(r32 * 2^-32 + t): the product is exact, so this is the single
+// rounding of t + r that the wire format prescribes, without forming r first.
+constexpr float kNearestOffset32 = 0x1p31f;
+__device__ __forceinline__ float offset32_from_word(uint32_t w) {
+    return static_cast<float>(w & 0xffffff00u);
+}
+
+// Rounding offsets (times 2^32) of one chunk whose first element has flat index j0
+// (a multiple of 8): block j0/4 feeds elements 0..3, block j0/4 + 1 elements 4..7.
 __device__ __forceinline__ void chunk_uniforms(uint64_t seed, uint64_t j0, float (&r)[kChunk]) {
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     const uint64_t blk = j0 >> 2;
     uint32_t w[4];
     philox4x32_10(static_cast<uint32_t>(blk), static_cast<uint32_t>(blk >> 32), k0, k1, w);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = uniform_from_word(w[e]);
+    for (int e = 0; e < 4; ++e) r[e] = offset32_from_word(w[e]);
     const uint64_t blk1 = blk + 1;
     philox4x32_10(static_cast<uint32_t>(blk1), static_cast<uint32_t>(blk1 >> 32), k0, k1, w);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[4 + e] = uniform_from_word(w[e]);
+    for (int e = 0; e < 4; ++e) r[4 + e] = offset32_from_word(w[e]);
 }
 
 // ---------------------------------------------------------------------------
@@ -318,22 +328,22 @@ __device__ __forceinline__ GroupScale scale_from_wire(float s_tx) {
     return g;
 }
 
-// Level of one value, kept as a float (an exact small integer); r = 1/2
-// (nearest, ties upwards) or U[0,1).
+// Level of one value, kept as a float (an exact small integer); the rounding offset
+// r = 1/2 (nearest, ties upwards) or U[0,1) arrives as r32 = r * 2^32 (see above).
 // y = ((d * inv) + L/2) + r is never below -2^-20, so rounding towards zero is
 // floor() followed by the clamp at 0 (a result of -0 counts as level 0 in all
 // that follows).  With r = 1/2, |d| <= s bounds y below L + 1, so no upper clamp
 // is needed; a stochastic r can reach L + 1.
 template <int BITS, int ROUND>
-__device__ __forceinline__ float level_of(float d, const GroupScale& g, float r) {
+__device__ __forceinline__ float level_of(float d, const GroupScale& g, float r32) {
     float t = d * g.inv;
     t = t + g.offset;
-    const float y = t + r;
-    const float k = __builtin_truncf(y);
-    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC)
-        return __builtin_fminf(k, static_cast<float>(Levels<BITS>::top));
-    else
-        return k;
+    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
+        const float y = __builtin_fmaf(r32, 0x1p-32f, t);          // RN(t + r): the product is exact
+        return __builtin_fminf(__builtin_truncf(y), static_cast<float>(Levels<BITS>::top));
+    } else {
+        return __builtin_truncf(t + 0.5f);
+    }
 }
 
 __device__ __forceinline__ float value_of(float level, const GroupScale& g) {
@@ -546,18 +556,18 @@ __device__ __forceinline__ uint32_t load_unit_codes(const uint8_t* p) {
     }
 }
 
-// Rounding offsets of two units whose first elements have flat indices ja and jb
-// (multiples of 4): one Philox block each.
+// Rounding offsets (times 2^32) of two units whose first elements have flat indices
+// ja and jb (multiples of 4): one Philox block each.
 __device__ __forceinline__ void units_uniforms(uint64_t seed, uint64_t ja, uint64_t jb, float (&r)[kChunk]) {
     const uint32_t k0 = static_cast<uint32_t>(seed), k1 = static_cast<uint32_t>(seed >> 32);
     const uint64_t blka = ja >> 2, blkb = jb >> 2;
     uint32_t w[4];
     philox4x32_10(static_cast<uint32_t>(blka), static_cast<uint32_t>(blka >> 32), k0, k1, w);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[e] = uniform_from_word(w[e]);
+    for (int e = 0; e < 4; ++e) r[e] = offset32_from_word(w[e]);
     philox4x32_10(static_cast<uint32_t>(blkb), static_cast<uint32_t>(blkb >> 32), k0, k1, w);
 #pragma unroll
-    for (int e = 0; e < 4; ++e) r[4 + e] = uniform_from_word(w[e]);
+    for (int e = 0; e < 4; ++e) r[4 + e] = offset32_from_word(w[e]);
 }
 
 }  // namespace aqsgd

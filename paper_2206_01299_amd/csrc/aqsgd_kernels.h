@@ -137,7 +137,7 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
                 chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
         } else {
 #pragma unroll
-            for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
+            for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
         }
         float q[kChunk], dh[kChunk];
 #pragma unroll

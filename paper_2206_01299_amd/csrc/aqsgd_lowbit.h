@@ -109,7 +109,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
                 chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
             } else {
 #pragma unroll
-                for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
+                for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
             }
             float q[kChunk];
 #pragma unroll
@@ -144,7 +144,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
     for (int k = 0; k < CPL; ++k) {
         float q[kChunk];
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) q[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, 0.5f);
+        for (int e = 0; e < kChunk; ++e) q[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, kNearestOffset32);
         store_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS, pack_levels<MBITS>(q));
         if constexpr (!SENDER) store_raw_at<DT>(out_s + goff * kEB + cc[k] * kChunkBytes, pack_raw<DT>(v[k]));
     }

@@ -270,7 +270,7 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
             chunk_uniforms(a.seed, static_cast<uint64_t>(e0) + static_cast<uint64_t>(cc[k]) * kChunk, r);
         } else {
 #pragma unroll
-            for (int e = 0; e < kChunk; ++e) r[e] = 0.5f;
+            for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
         }
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
