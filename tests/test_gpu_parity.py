@@ -25,15 +25,6 @@ def H():
     return gpu_harness
 
 
-@pytest.fixture(autouse=True)
-def _release_device_memory():
-    """The big buffers of one test must not crowd out the next one's."""
-    yield
-    if torch.cuda.is_available():
-        torch.cuda.synchronize()
-        torch.cuda.empty_cache()
-
-
 # ---------------------------------------------------------------------------
 # element-by-element sweeps at sizes the oracle finishes in well under a second:
 # every dtype x bits x rounding, group sizes that hit every kernel shape
