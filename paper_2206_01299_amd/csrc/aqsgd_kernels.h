@@ -106,6 +106,24 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
     // otherwise sink them next to their consumers and leave two or three in flight.
     __builtin_amdgcn_sched_barrier(0);
 
+    // ---- rounding offsets: they depend on the element index only, so the generator
+    //      runs while the loads are in flight (second barrier: it stays up here) -------
+    float r[CPL][kChunk];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
+            if constexpr (kUnits)
+                units_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + ua[k] * kUnit,
+                               static_cast<uint64_t>(src0 + goff) + ub[k] * kUnit, r[k]);
+            else
+                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r[k]);
+        } else {
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) r[k][e] = kNearestOffset32;
+        }
+    }
+    if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) __builtin_amdgcn_sched_barrier(0);
+
     // ---- delta and the group's max-abs --------------------------------------------
     float d[CPL][kChunk];
     float mx = 0.0f;
@@ -128,21 +146,10 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
     // ---- quantise, pack, update m ---------------------------------------------------
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        float r[kChunk];
-        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
-            if constexpr (kUnits)
-                units_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + ua[k] * kUnit,
-                               static_cast<uint64_t>(src0 + goff) + ub[k] * kUnit, r);
-            else
-                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
-        } else {
-#pragma unroll
-            for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
-        }
         float q[kChunk], dh[kChunk];
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
-            q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[e]);
+            q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[k][e]);
             dh[e] = value_of(q[e], sc);
         }
         uint8_t* group_codes = codes_s + goff / kChunk * BITS;
