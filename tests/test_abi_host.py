@@ -100,3 +100,32 @@ def test_binding_has_no_cpu_route():
                  torch.zeros(1))
     src = (ROOT / "paper_2206_01299_amd" / "binding.py").read_text()
     assert "import oracle" not in src and "from oracle" not in src
+
+
+def test_header_is_plain_c_and_a_c_client_links(tmp_path):
+    """The boundary is a C ABI: the header compiles as C99 on its own, and a C program
+    that only knows the header links against the library and reads a size through it."""
+    import ctypes.util
+    import shutil
+    import subprocess
+    from pathlib import Path
+    root = Path(__file__).resolve().parent.parent
+    header = root / "include" / "aqsgd.h"
+    gcc = shutil.which("gcc")
+    assert gcc, "gcc is part of the image"
+    subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-pedantic", "-Werror", "-fsyntax-only", "-x", "c",
+                    str(header)], check=True)
+    lib = root / "paper_2206_01299_amd" / "libaqsgd.so"
+    src = tmp_path / "client.c"
+    src.write_text('#include <stdio.h>\n#include "aqsgd.h"\n'
+                   'int main(void) {\n'
+                   '    aqsgd_desc d = {4, 1638400, 8192, 4, 1600, AQSGD_F16, AQSGD_ROUND_NEAREST, 0};\n'
+                   '    printf("%zu %zu %s\\n", aqsgd_codes_bytes(&d), aqsgd_scales_count(&d), aqsgd_strerror(-3));\n'
+                   '    return aqsgd_encode(&d, NULL, NULL, NULL, NULL, NULL, NULL) == AQSGD_ERR_NULL ? 0 : 1;\n'
+                   '}\n')
+    exe = tmp_path / "client"
+    subprocess.run([gcc, "-std=c99", f"-I{header.parent}", str(src), str(lib), f"-Wl,-rpath,{lib.parent}",
+                    "-Wl,-rpath,/opt/rocm/lib", "-o", str(exe)], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=2)
+    assert out[0] == str(4 * 1638400 * 4 // 8) and out[1] == str(4 * 1638400 // 1600)
+    assert "group" in out[2]
