@@ -462,7 +462,10 @@ def main():
         print("bench.py: no GPU visible; the codec has no CPU path.", file=sys.stderr)
         sys.exit(3)
     from paper_2206_01299_amd import binding as B
+    from paper_2206_01299_amd import build as _build
     from paper_2206_01299_amd import workloads as W
+    if not _build.LIB.exists():          # load what is built; build only if nothing is
+        _build.build(verbose=False)
     B.lib()
 
     cfg = {"gpt2_4bit": W.gpt2_4bit, "gpt2_2bit_stochastic": W.gpt2_2bit_stochastic,
