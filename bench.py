@@ -17,8 +17,12 @@ the 256 MB of last-level cache, so every call reads cold rows from HBM.  The
 buffers are pre-seeded by one full pass and the activations then drift by
 0.05 sigma, so the timed steps encode changes, as in steady-state fine-tuning.
 
-The K timed steps are recorded into HIP graphs (256 steps each) and replayed
-back to back, bracketed by device synchronisation; wall time / K is ms_per_step.
+The K timed steps are recorded into HIP graphs (256 steps each), replayed once
+untimed (the first replay of a new graph uploads it), and then replayed back to back
+between two HIP events on the launching stream, with device synchronisation on both
+sides; event time / K is ms_per_step.  `value` is the metric's own quantity: the
+activation bytes of a micro-batch over the time of its encode + decode, from a second
+timed run of the same K micro-batches without the backward message.
 Micro-batches touch disjoint samples and pool slots, so their codec calls are
 independent, as they are in a pipeline stage that has several micro-batches in
 flight: with --streams N (default 4) the forward pairs (encode then decode) are
@@ -165,6 +169,7 @@ class Workload:
         perm = torch.randperm(cfg.n_samples, generator=g, device=d)
         self.ids = perm.view(-1, Bn).contiguous()              # [calls per epoch, B]
         self.calls = self.ids.shape[0]
+        self.evict = torch.zeros(1 << 28, dtype=torch.int32, device=d)     # 1 GiB, see evict_caches()
         torch.cuda.synchronize()
 
     def _draw(self, shape):
@@ -283,12 +288,63 @@ class Workload:
         }
 
 
+class DeviceClock:
+    """Times work queued on one stream with a HIP event pair recorded on that stream.
+
+    The host cannot enqueue as fast as the GPU drains a few hundred microseconds of
+    kernels, so a bracket taken on an idle stream would also hold the host's launch
+    latency.  Here a spin kernel is queued first; while it runs the host records the
+    start event, enqueues all the work and records the stop event, so when the spin
+    ends the stream goes through start, the work and stop back to back and the event
+    pair holds device time only.  Every kernel of the timed region lies between the two
+    events; a wall clock around the same region (synchronised on both sides) is reported
+    next to it."""
+
+    def __init__(self, torch, stream):
+        self.torch, self.stream = torch, stream
+        # how long one million spin cycles take on this device
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        with torch.cuda.stream(stream):
+            torch.cuda._sleep(1_000_000)
+            a.record(stream)
+            torch.cuda._sleep(1_000_000)
+            b.record(stream)
+        torch.cuda.synchronize()
+        self.cycles_per_ms = 1_000_000 / max(a.elapsed_time(b), 1e-3)
+
+    def time(self, enqueue, hold_ms=2.0):
+        """enqueue() queues the work on self.stream.  Returns (device seconds, wall seconds)."""
+        torch = self.torch
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(self.stream):
+            torch.cuda._sleep(int(hold_ms * self.cycles_per_ms))
+            a.record(self.stream)
+            enqueue()
+            b.record(self.stream)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0 - hold_ms * 1e-3
+        return a.elapsed_time(b) * 1e-3, wall
+
+
+def evict_caches(torch, scratch):
+    """Overwrite 1 GiB, four times the last-level cache, so that the next kernels find
+    none of their rows cached."""
+    scratch.add_(1)
+    torch.cuda.synchronize()
+
+
 def timed_steps(wl, first, count, launch, n_streams, backward=True):
-    """Run `count` steps starting at step index `first`; returns wall seconds."""
+    """Run `count` steps starting at step index `first`; returns (device seconds, wall
+    seconds) of the whole region.  In graph mode the graphs are built, instantiated and
+    replayed once before the clock starts (the first replay of a new graph uploads it);
+    the caches are then evicted, so the timed replay reads cold rows again."""
     torch = wl.torch
     main = torch.cuda.Stream()
     if n_streams > 1:
         wl.make_streams(n_streams)
+    clock = DeviceClock(torch, main)
 
     def enqueue(k0, k1):
         """Steps k0..k1-1 onto `main` (one stream) or fanned out from / joined back into it."""
@@ -308,12 +364,8 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True):
             main.wait_event(done)
 
     if launch == "eager":
-        torch.cuda.synchronize()
-        t0 = time.perf_counter()
-        with torch.cuda.stream(main):
-            enqueue(first, first + count)
-        torch.cuda.synchronize()
-        return time.perf_counter() - t0
+        # the spin must outlast the host's enqueueing of every launch (about 10 us each)
+        return clock.time(lambda: enqueue(first, first + count), hold_ms=2.0 + 0.05 * count)
     graphs = []
     k = first
     while k < first + count:
@@ -323,12 +375,15 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True):
             enqueue(k, k + m)
         graphs.append(g)
         k += m
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for g in graphs:
-        g.replay()
-    torch.cuda.synchronize()
-    return time.perf_counter() - t0
+    with torch.cuda.stream(main):
+        for g in graphs:                                 # untimed: uploads the graphs
+            g.replay()
+    evict_caches(torch, wl.evict)
+
+    def replay_all():
+        for g in graphs:
+            g.replay()
+    return clock.time(replay_all)
 
 
 def hot_forward_pairs(wl, k, count):
@@ -340,12 +395,30 @@ def hot_forward_pairs(wl, k, count):
     with torch.cuda.graph(g, stream=main):
         for _ in range(count):
             wl.step(k, backward=False)
-    g.replay()
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    g.replay()
-    torch.cuda.synchronize()
-    return (time.perf_counter() - t0) / count
+    with torch.cuda.stream(main):
+        g.replay()
+    dev, _ = DeviceClock(torch, main).time(g.replay)
+    return dev / count
+
+
+def one_stream_forward_pairs(wl, first, count=256, warm=20):
+    """The forward message on ONE stream: `count` encode -> decode pairs of successive
+    cold micro-batches, strictly one kernel after the other, after `warm` untimed pairs;
+    HIP events around the pairs.  Seconds per pair."""
+    torch = wl.torch
+    main = torch.cuda.Stream()
+    with torch.cuda.stream(main):
+        for k in range(first, first + warm):
+            wl.step(k, backward=False)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=main):
+        for k in range(first + warm, first + warm + count):
+            wl.step(k, backward=False)
+    with torch.cuda.stream(main):
+        g.replay()
+    evict_caches(torch, wl.evict)
+    dev, _ = DeviceClock(torch, main).time(g.replay)
+    return dev / count
 
 
 def stream_copy_ceiling(torch, nbytes=1 << 30, reps=5):
@@ -392,46 +465,56 @@ def kernel_legs(wl, first, count):
 
 
 def cpu_baseline(cfg, calls):
-    """The oracle, as it stands, on this machine's host cores: the same four
-    calls on full-shape micro-batches of the same workload."""
+    """The oracle, as it stands, on this machine's host cores: the forward message
+    (encode + decode, the metric's quantity) and the whole step on full-shape
+    micro-batches of the same workload, each micro-batch with its own samples.  The
+    samples are seeded by one untimed visit first, so the timed calls encode changes.
+    Median over the micro-batches."""
     import numpy as np
     import oracle
+    from oracle.boundary import OracleBoundary
     from paper_2206_01299_amd import workloads as W
-    import gpu_harness as H
     oracle.build()
     threads = oracle.max_threads()
-    visited = W.parity_ids(cfg, 1)
+    n_mb = calls if calls > 0 else 8
+    visited = W.parity_ids(cfg, n_mb)
     stream = W.ActivationStream(cfg, visited=visited)
-    cpu = H.OracleBoundary(cfg, visited)
-    ids = stream.epoch_ids(0)[0]
-    acts = [stream.activations(ids, t) for t in range(2)]
-    grad = stream.gradients(ids, 0)
-    cpu.forward(acts[0], ids, 0)                                   # seed m: later calls send changes
-    t_once = time.perf_counter()
-    cpu.forward(acts[1], ids, 1)
-    cpu.backward(grad, 1)
-    t_once = time.perf_counter() - t_once
-    if calls <= 0:
-        calls = max(1, min(64, int(15.0 / max(t_once, 1e-3))))
-    t0 = time.perf_counter()
-    for i in range(calls):
-        cpu.forward(acts[i % 2], ids, i)
-        cpu.backward(grad, i)
-    dt = (time.perf_counter() - t0) / calls
-    oracle.set_threads(1)                                          # the same step on one thread
-    one_calls = max(1, min(8, int(5.0 / max(dt * threads, 1e-3))))
-    t0 = time.perf_counter()
-    for i in range(one_calls):
-        cpu.forward(acts[i % 2], ids, calls + i)
-        cpu.backward(grad, calls + i)
-    dt1 = (time.perf_counter() - t0) / one_calls
+    cpu = OracleBoundary(cfg, visited)
+    batches = stream.epoch_ids(0)
+    grads = [stream.gradients(ids, 0) for ids in batches]
+    for k, ids in enumerate(batches):                              # seed m: later calls send changes
+        cpu.forward(stream.activations(ids, 0), ids, k)
+    acts = [stream.activations(ids, 1) for ids in batches]
+
+    def run(first_seed):
+        fwd, step = [], []
+        for k, ids in enumerate(batches):
+            t0 = time.perf_counter()
+            cpu.forward(acts[k], ids, first_seed + k)
+            t1 = time.perf_counter()
+            cpu.backward(grads[k], first_seed + k)
+            t2 = time.perf_counter()
+            fwd.append(t1 - t0)
+            step.append(t2 - t0)
+        return float(np.median(fwd)), float(np.median(step))
+
+    fwd, step = run(1000)
+    oracle.set_threads(1)                                          # the same on one thread
+    one = min(n_mb, max(2, int(6.0 / max(step * threads, 1e-3))))
+    keep = batches
+    batches = batches[:one]
+    fwd1, step1 = run(2000)
+    batches = keep
     oracle.set_threads(threads)
-    return {"value": cfg.n * cfg.elem_bytes / dt / 1e9, "unit": "GB/s", "cores": threads,
-            "kind": "oracle", "ms_per_step": dt * 1e3,
-            "one_thread": {"value": round(cfg.n * cfg.elem_bytes / dt1 / 1e9, 4),
-                           "ms_per_step": round(dt1 * 1e3, 1), "steps": one_calls},
-            "sample": f"{calls} full-shape steps (encode+decode+grad_quant+grad_dequant) of "
-                      f"{cfg.name}, 1 micro-batch of {cfg.batch} samples revisited, OpenMP over groups"}
+    act_bytes = cfg.n * cfg.elem_bytes
+    return {"value": act_bytes / fwd / 1e9, "unit": "GB/s", "cores": threads, "kind": "oracle",
+            "ms_per_fwd_pair": fwd * 1e3, "ms_per_step": step * 1e3,
+            "step_act_GBps": round(act_bytes / step / 1e9, 4),
+            "one_thread": {"value": round(act_bytes / fwd1 / 1e9, 4), "ms_per_fwd_pair": round(fwd1 * 1e3, 1),
+                           "ms_per_step": round(step1 * 1e3, 1), "microbatches": one},
+            "sample": f"{n_mb} distinct full-shape micro-batches of {cfg.name} ({cfg.batch} samples each), "
+                      f"second visit of every sample; value = activation bytes / median time of "
+                      f"encode + decode; OpenMP over groups"}
 
 
 def read_traffic():
@@ -490,13 +573,12 @@ def main():
         wl.step(k)
     torch.cuda.synchronize()
 
-    wall = timed_steps(wl, Wm, K, args.launch, args.streams)
-    ms_per_step = wall / K * 1e3
+    # K whole steps, then the forward messages of the same K micro-batches alone
+    step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams)
+    fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False)
+    ms_per_step = step_dev / K * 1e3
     act_bytes = cfg.n * cfg.elem_bytes
-    value = act_bytes / (wall / K) / 1e9
-
-    # forward messages alone (encode + decode of K micro-batches), same launch mode
-    fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False)
+    value = act_bytes / (fwd_dev / K) / 1e9              # the metric: encode + decode, activation bytes
 
     legs = None if args.no_kernel_legs else kernel_legs(wl, Wm, K)
     lb = wl.leg_bytes()
@@ -511,7 +593,9 @@ def main():
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
                     "algorithmic_bytes_per_launch": lb[dominant],
                     "avg_launch_us": round(legs[dominant]["avg_us"], 3),
-                    "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch")}
+                    "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch"),
+                    "traffic_source": "stored rocprofv3 counter value (profiles/hbm_traffic_gpt2_fw4.txt), "
+                                      "not measured in this run" if traffic else None}
         pair_us = legs["encode"]["avg_us"] + legs["decode"]["avg_us"]
         pair_bytes = lb["encode"] + lb["decode"]
         extra["fwd_pair_isolated_launches"] = {"us": round(pair_us, 3),
@@ -522,13 +606,23 @@ def main():
                                 "median_us": round(legs[l]["median_us"], 3),
                                 "hbm_GBps": round(lb[l] / legs[l]["avg_us"] / 1e3, 1)} for l in wl.LEGS}
     fwd_bytes = lb["encode"] + lb["decode"]
-    extra["fwd_only"] = {"us_per_microbatch": round(fwd_wall / K * 1e6, 3),
-                         "act_GBps": round(act_bytes / (fwd_wall / K) / 1e9, 1),
-                         "hbm_GBps": round(fwd_bytes / (fwd_wall / K) / 1e9, 1),
-                         "frac_of_hbm_peak": round(fwd_bytes / (fwd_wall / K) / 1e9 / HBM_PEAK_GBPS, 4)}
     step_bytes = sum(lb.values())
-    extra["step_hbm_GBps"] = round(step_bytes / (wall / K) / 1e9, 1)
-    extra["step_frac_of_hbm_peak"] = round(step_bytes / (wall / K) / 1e9 / HBM_PEAK_GBPS, 4)
+    extra["fwd_only"] = {"us_per_microbatch": round(fwd_dev / K * 1e6, 3),
+                         "act_GBps": round(value, 1),
+                         "hbm_GBps": round(fwd_bytes / (fwd_dev / K) / 1e9, 1),
+                         "frac_of_hbm_peak": round(fwd_bytes / (fwd_dev / K) / 1e9 / HBM_PEAK_GBPS, 4),
+                         "wall_us_per_microbatch": round(fwd_wall / K * 1e6, 3)}
+    extra["whole_step"] = {"us": round(step_dev / K * 1e6, 3),
+                           "act_GBps": round(act_bytes / (step_dev / K) / 1e9, 1),
+                           "hbm_GBps": round(step_bytes / (step_dev / K) / 1e9, 1),
+                           "frac_of_hbm_peak": round(step_bytes / (step_dev / K) / 1e9 / HBM_PEAK_GBPS, 4),
+                           "wall_us": round(step_wall / K * 1e6, 3)}
+    one = one_stream_forward_pairs(wl, Wm + K)
+    extra["fwd_one_stream"] = {"us_per_microbatch": round(one * 1e6, 3),
+                               "act_GBps": round(act_bytes / one / 1e9, 1),
+                               "frac_of_hbm_peak": round(fwd_bytes / one / 1e9 / HBM_PEAK_GBPS, 4),
+                               "note": "256 encode -> decode pairs of cold micro-batches on one stream after 20 "
+                                       "untimed pairs, HIP events around them"}
     hot = hot_forward_pairs(wl, Wm, 256)
     extra["fwd_hot_buffers_footnote"] = {"us_per_microbatch": round(hot * 1e6, 3),
                                          "note": "one micro-batch repeated on one stream: rows stay in the "
@@ -539,6 +633,7 @@ def main():
     if not args.no_cpu_baseline:
         base = cpu_baseline(cfg, args.cpu_calls)
         base["value"] = round(base["value"], 4)
+        base["ms_per_fwd_pair"] = round(base["ms_per_fwd_pair"], 2)
         base["ms_per_step"] = round(base["ms_per_step"], 2)
 
     line = {
@@ -546,9 +641,17 @@ def main():
         "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
         "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "f32", "data": "synthetic",
-        "config": {"workload": WORKLOAD_TEXT[args.config] + "; one step = encode + decode + grad_quant + "
-                               "grad_dequant; value = activation bytes of one micro-batch / step time",
+        "config": {"workload": WORKLOAD_TEXT[args.config],
                    "name": cfg.name,
+                   "step": "encode + decode + grad_quant + grad_dequant of one micro-batch (ms_per_step)",
+                   "value_is": "activation bytes of one micro-batch / time of its encode + decode "
+                               "(the metric's quantity), from a second timed run of the same K "
+                               "micro-batches without the backward message; the whole step is under "
+                               "whole_step",
+                   "timing": "HIP events on the launching stream around the replays of HIP graphs that "
+                             "were instantiated and replayed once beforehand, queued behind a spin kernel "
+                             "so that host launch latency is outside the bracket; caches evicted before "
+                             "the timed replay; every kernel of all K steps is inside",
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
                    "group": cfg.fwd_group, "m_bits": args.m_bits or None, "bwd_keep": args.bwd_keep or None,

@@ -18,9 +18,14 @@
  *
  * General rules for every entry point
  *   - Every data pointer is DEVICE memory on the current HIP device, owned by the
- *     caller before, during and after the call; the library allocates nothing,
- *     keeps no state between calls and may be called from several host threads.
- *     The descriptor is HOST memory and is read before the call returns.
+ *     caller before, during and after the call.  The codec calls allocate no device
+ *     memory, keep no state between calls and may be made from several host threads
+ *     at once.  Descriptors and job lists are HOST memory and are read before the
+ *     call returns.  Three things are stateful, and say so where they are declared:
+ *     the launch-shape knobs (process-wide atomics, aqsgd_set_launch_shape), the
+ *     request to time the next launch (per host thread, aqsgd_profile_next_launch)
+ *     and the host-memory tier (an object that owns events, a worker thread and
+ *     host bookkeeping, aqsgd_tier_*).
  *   - Calls only enqueue work on `stream` (a hipStream_t passed as void*; NULL is
  *     the default stream) and return; results are valid once the stream reaches
  *     that point.  Ordering between a sender's and a receiver's stream is the
@@ -37,10 +42,12 @@
  *   - Alignment: act, grad, out, m_buf and codes 16 bytes, scales 4, ids 8.
  *   - Return value: AQSGD_OK or a negative aqsgd_status.  Everything the host can
  *     check is checked before any work is enqueued; on error nothing is enqueued.
- *     NOT checked (undefined results, but no out-of-bounds access as long as ids
- *     are in range): sample ids outside [0, n_samples), duplicate ids within one
- *     call (two rows of the call would race on one row of m_buf), non-finite
- *     inputs.  aqsgd_check_ids() checks the first two on the device.
+ *     NOT checked: sample ids outside [0, n_samples) (out-of-bounds accesses),
+ *     duplicate ids within one call (two rows of the call race on one row of
+ *     m_buf: undefined results, all accesses in bounds), non-finite inputs
+ *     (undefined results), buffers smaller than the descriptor says.
+ *     aqsgd_check_ids() checks the first two on the device.  AQSGD_ERR_LAUNCH
+ *     reports the status of the call's own launch.
  *   - Arithmetic is IEEE binary32 with one rounding per operation and no fused
  *     multiply-add; stores to float16/bfloat16 round to nearest-even.  Results are
  *     bit-identical for any launch configuration.
@@ -128,6 +135,50 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
                        void* out, void* stream);
 
 /*
+ * Several independent messages in as few launches as possible.
+ *
+ * The two stages of a boundary each have two kinds of message to handle at about the
+ * same time (Algorithm 2: network a sends the activation change and reconstructs the
+ * returned gradient, network b reconstructs the activation and sends the gradient), a
+ * stage in the middle of a pipeline has two boundaries, and Appendix A.1's K machines
+ * are K-1 independent instances.  A launch of a few tens of MB spends a good part of its
+ * time filling and draining the GPU, so messages that are ready together should share a
+ * grid.  Each job is exactly one of the four calls above, with the same arguments,
+ * meaning, alignment and preconditions:
+ *   AQSGD_JOB_ENCODE        src = act,  sample_ids, m_buf (i/o), codes and scales (out)
+ *   AQSGD_JOB_DECODE        codes and scales (in), sample_ids, m_buf (i/o), out
+ *   AQSGD_JOB_GRAD_QUANT    src = grad, codes and scales (out)
+ *   AQSGD_JOB_GRAD_DEQUANT  codes and scales (in), out
+ * Unused pointers of a job are ignored.  The jobs of one call must be independent: none
+ * reads what another writes, and no two touch the same row of the same m_buf; they run
+ * concurrently, in no particular order.  Results are bit-identical to the single calls.
+ * How jobs share launches: quantising jobs (ENCODE, GRAD_QUANT) with the same dtype,
+ * bits, rounding and group-size class share one grid, and the dequantising jobs of that
+ * dtype join it; dequantising jobs without such a host share a grid of their own; up to
+ * 8 + 8 jobs per grid, more are split; jobs whose group is not a multiple of 8 or larger
+ * than 32768 run on their own.  The typical stage-side call (one ENCODE and one
+ * GRAD_DEQUANT, or one DECODE and one GRAD_QUANT) is one launch.
+ * Every job is checked first; on an error (the first bad job's status, or
+ * AQSGD_ERR_SHAPE for an unknown kind or a negative count) nothing is enqueued.
+ */
+typedef enum {
+    AQSGD_JOB_ENCODE = 0, AQSGD_JOB_DECODE = 1, AQSGD_JOB_GRAD_QUANT = 2, AQSGD_JOB_GRAD_DEQUANT = 3
+} aqsgd_job_kind;
+
+typedef struct {
+    int32_t kind;                 /* aqsgd_job_kind                                   */
+    aqsgd_desc desc;
+    const void* src;              /* act (ENCODE) or grad (GRAD_QUANT)                */
+    const int64_t* sample_ids;    /* ENCODE, DECODE                                   */
+    void* m_buf;                  /* ENCODE, DECODE                                   */
+    uint8_t* codes;               /* written by the quantising, read by the other jobs */
+    float* scales;
+    void* out;                    /* DECODE, GRAD_DEQUANT                             */
+} aqsgd_job;
+
+int aqsgd_run_jobs(const aqsgd_job* jobs, int32_t n_jobs, void* stream);
+
+/*
  * Uncompressed first visit (Algorithm 1's branch for a sample without a previous
  * message; Appendix D runs a whole warm-up epoch this way): the message is the
  * activation itself, at full precision, and both stages store it as m(xi).
@@ -146,27 +197,35 @@ int aqsgd_seed(const aqsgd_desc* desc, const void* act, const int64_t* sample_id
 /*
  * Algorithm 1 with its first-visit branch (a sample without a previous message: the
  * activation is sent in full precision and m(xi) <- a(xi); otherwise the quantised
- * change is sent).
- * `seen` holds one byte per sample of m_buf (0 = no previous message yet); both stages
- * keep their own copy, which stay identical because both see the same sample ids.
- *   aqsgd_encode_seen   samples with seen == 0: m_buf[id] <- act[i], first[i] = 1, their
- *                       slices of codes / scales are NOT written (row i of act is the
- *                       message); other samples: exactly aqsgd_encode, first[i] = 0
- *   aqsgd_decode_seen   samples with seen == 0: m_buf[id] <- full[i], out[i] <- full[i];
+ * change is sent).  One launch per call.
+ * `seen` holds one 32-bit word per sample of m_buf, zero-initialised by the caller:
+ * 0 = no previous message yet, otherwise the stamp of the call that first visited the
+ * sample.  Every call carries a `stamp` of the caller's choosing that is not 0 and
+ * that no earlier call on this buffer has used (a running call counter does); a sample
+ * is new to a call if its word is 0.  Both stages keep their own `seen`; they stay
+ * identical (as zero / non-zero patterns) because both see the same sample ids.  The
+ * stamps of the two stages need not agree.  Reusing a stamp makes the samples first
+ * visited under it count as new once more (they are sent in full again: wasteful, but
+ * both stages still agree as long as they reuse alike).
+ *   aqsgd_encode_seen   new samples: m_buf[id] <- act[i], first[i] = 1, their slices of
+ *                       codes / scales are NOT written (row i of act is the message);
+ *                       other samples: exactly aqsgd_encode, first[i] = 0
+ *   aqsgd_decode_seen   new samples: m_buf[id] <- full[i], out[i] <- full[i];
  *                       other samples: exactly aqsgd_decode (their rows of full are not read)
- * Both mark every sample of the call as seen afterwards.
- *   seen    i/o  uint8[n_samples], device
+ * Both store the call's stamp in the words of the new samples.
+ *   seen    i/o  uint32[n_samples], device, 4-byte aligned
+ *   stamp   in   non-zero (else AQSGD_ERR_SHAPE)
  *   first   out  int32[batch], device, 4-byte aligned
  *   full    in   [batch, n_per] of desc.dtype, 16-byte aligned: the uncompressed rows
  * Everything else (arguments, alignment, preconditions, status codes) as in
- * aqsgd_encode / aqsgd_decode.  Each call enqueues three kernels on `stream`.
+ * aqsgd_encode / aqsgd_decode.
  */
 int aqsgd_encode_seen(const aqsgd_desc* desc, const void* act, const int64_t* sample_ids,
-                      void* m_buf, uint8_t* seen, int32_t* first, uint8_t* codes, float* scales,
-                      void* stream);
+                      void* m_buf, uint32_t* seen, uint32_t stamp, int32_t* first, uint8_t* codes,
+                      float* scales, void* stream);
 int aqsgd_decode_seen(const aqsgd_desc* desc, const uint8_t* codes, const float* scales,
-                      const void* full, const int64_t* sample_ids, void* m_buf, uint8_t* seen,
-                      void* out, void* stream);
+                      const void* full, const int64_t* sample_ids, void* m_buf, uint32_t* seen,
+                      uint32_t stamp, void* out, void* stream);
 
 /*
  * Previous messages kept at low precision ("m z", Appendix H.5: z bits for the
@@ -267,18 +326,19 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
                     int32_t* flag, void* stream);
 
 /*
- * Tuning helper: how launches are cut into workgroups, for the whole process.  It never
- * changes a result bit.  max_blocks bounds the workgroups of one launch (kernels loop
+ * Tuning helper (process-wide state): how launches are cut into workgroups.  It never
+ * changes a result bit.  max_blocks bounds the workgroups of one job (kernels loop
  * when it is smaller than the work), dequant_unroll (1, 2 or 4) is the number of chunks a
- * lane of the dequantising kernel takes per step; 0 restores the value from the
- * environment (AQSGD_MAX_BLOCKS, AQSGD_DEQUANT_UNROLL) or the built-in default.  Not to
- * be called while another host thread is inside a codec call.  AQSGD_ERR_SHAPE for values
- * out of range.
+ * lane takes per step in a launch that holds dequantising jobs only; 0 restores the value
+ * from the environment (AQSGD_MAX_BLOCKS, AQSGD_DEQUANT_UNROLL) or the built-in default.
+ * The two settings are atomics, read once per call: a change made while another host
+ * thread is inside a codec call applies to that thread's next call.  AQSGD_ERR_SHAPE for
+ * values out of range.
  */
 int aqsgd_set_launch_shape(int64_t max_blocks, int32_t dequant_unroll);
 
 /*
- * Measurement helper: the next codec launch made by the calling host thread
+ * Measurement helper (per-thread state): the next codec launch made by the calling host thread
  * stamps `start_event` and `stop_event` (hipEvent_t created with timing enabled,
  * passed as void*; either may be NULL) with the kernel's own begin and end, so
  * hipEventElapsedTime(start, stop) is that launch's duration on the device.  The

@@ -22,7 +22,7 @@ DTYPE_CODE = {torch.float32: F32, torch.float16: F16, torch.bfloat16: BF16}
 DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16}
 
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
-           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_seed", "aqsgd_encode_seen",
+           "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_run_jobs", "aqsgd_seed", "aqsgd_encode_seen",
            "aqsgd_decode_seen", "aqsgd_lowbit_row_bytes",
            "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
            "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
@@ -36,6 +36,16 @@ class Desc(ctypes.Structure):
     _fields_ = [("batch", ctypes.c_int64), ("n_per", ctypes.c_int64), ("n_samples", ctypes.c_int64),
                 ("bits", ctypes.c_int32), ("group", ctypes.c_int32), ("dtype", ctypes.c_int32),
                 ("rounding", ctypes.c_int32), ("rng_seed", ctypes.c_uint64)]
+
+
+JOB_ENCODE, JOB_DECODE, JOB_GRAD_QUANT, JOB_GRAD_DEQUANT = 0, 1, 2, 3
+
+
+class Job(ctypes.Structure):
+    """Mirror of ``aqsgd_job``."""
+    _fields_ = [("kind", ctypes.c_int32), ("desc", Desc), ("src", ctypes.c_void_p),
+                ("sample_ids", ctypes.c_void_p), ("m_buf", ctypes.c_void_p), ("codes", ctypes.c_void_p),
+                ("scales", ctypes.c_void_p), ("out", ctypes.c_void_p)]
 
 
 class AqsgdError(RuntimeError):
@@ -72,9 +82,11 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_seed.restype = ctypes.c_int
         L.aqsgd_seed.argtypes = [dp, vp, vp, vp, vp]
         L.aqsgd_encode_seen.restype = ctypes.c_int
-        L.aqsgd_encode_seen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_encode_seen.argtypes = [dp, vp, vp, vp, vp, ctypes.c_uint32, vp, vp, vp, vp]
         L.aqsgd_decode_seen.restype = ctypes.c_int
-        L.aqsgd_decode_seen.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.aqsgd_decode_seen.argtypes = [dp, vp, vp, vp, vp, vp, vp, ctypes.c_uint32, vp, vp]
+        L.aqsgd_run_jobs.restype = ctypes.c_int
+        L.aqsgd_run_jobs.argtypes = [ctypes.POINTER(Job), ctypes.c_int32, vp]
         L.aqsgd_lowbit_row_bytes.restype = ctypes.c_size_t
         L.aqsgd_lowbit_row_bytes.argtypes = [dp, ctypes.c_int32]
         L.aqsgd_encode_lowbit.restype = ctypes.c_int
@@ -149,6 +161,55 @@ def _dev(t: torch.Tensor, what: str) -> ctypes.c_void_p:
     return ctypes.c_void_p(t.data_ptr())
 
 
+_TORCH_OF_CODE = {code: dt for dt, code in DTYPE_CODE.items()}
+
+# When set (``check_ids_always(True)``), every call that takes sample ids first runs
+# ``aqsgd_check_ids`` on them and waits for its verdict: a debugging aid, it
+# synchronises the stream.
+_debug_ids = False
+
+
+def check_ids_always(on: bool = True) -> None:
+    global _debug_ids
+    _debug_ids = bool(on)
+
+
+def _want(t: torch.Tensor, what: str, dtype, numel: int, exact: bool) -> None:
+    """The kernels index these tensors from the descriptor alone; a tensor of another
+    element type or a smaller size would be read or written out of bounds."""
+    if t.dtype != dtype:
+        raise ValueError(f"{what} must be {dtype}, got {t.dtype}")
+    if (t.numel() != numel) if exact else (t.numel() < numel):
+        raise ValueError(f"{what} must hold {'exactly' if exact else 'at least'} {numel} elements, "
+                         f"got {t.numel()}")
+
+
+def _check(desc: Desc, *, rows=(), ids=None, m_buf=None, codes=None, scales=None, stream=None) -> None:
+    """Shapes and element types of one codec call against its descriptor.
+    ``rows``: (tensor, name) pairs of [batch, n_per] tensors in the descriptor's dtype."""
+    if desc.dtype not in _TORCH_OF_CODE:
+        return                                  # the library reports the bad descriptor
+    td = _TORCH_OF_CODE[desc.dtype]
+    n = desc.batch * desc.n_per
+    for t, what in rows:
+        _want(t, what, td, n, exact=True)
+    if m_buf is not None:
+        _want(m_buf, "m_buf", td, desc.n_samples * desc.n_per, exact=True)
+    if ids is not None:
+        _want(ids, "sample_ids", torch.int64, desc.batch, exact=True)
+    if codes is not None:
+        _want(codes, "codes", torch.uint8, codes_bytes(desc), exact=False)
+    if scales is not None:
+        _want(scales, "scales", torch.float32, scales_count(desc), exact=False)
+    if ids is not None and _debug_ids and desc.batch > 0:
+        flag = torch.zeros(1, dtype=torch.int32, device=ids.device)
+        check_ids(ids, desc.n_samples, flag, stream)
+        bad = int(flag.item())
+        if bad:
+            raise ValueError("sample_ids: " + " and ".join(
+                w for b, w in ((1, "an id is outside [0, n_samples)"), (2, "two ids are equal")) if bad & b))
+
+
 def _raise(status: int):
     if status != 0:
         raise AqsgdError(status, strerror(status))
@@ -156,6 +217,7 @@ def _raise(status: int):
 
 def encode(desc: Desc, act, sample_ids, m_buf, codes, scales, stream=None) -> None:
     """``aqsgd_encode``: updates ``m_buf`` in place, fills ``codes`` and ``scales``."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales, stream=stream)
     _raise(lib().aqsgd_encode(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
                               _dev(m_buf, "m_buf"), _dev(codes, "codes"), _dev(scales, "scales"),
                               _stream(stream)))
@@ -163,48 +225,108 @@ def encode(desc: Desc, act, sample_ids, m_buf, codes, scales, stream=None) -> No
 
 def decode(desc: Desc, codes, scales, sample_ids, m_buf, out, stream=None) -> None:
     """``aqsgd_decode``: updates ``m_buf`` in place, fills ``out``."""
+    _check(desc, rows=[(out, "out")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales, stream=stream)
     _raise(lib().aqsgd_decode(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
                               _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"), _dev(out, "out"),
                               _stream(stream)))
 
 
 def grad_quant(desc: Desc, grad, codes, scales, stream=None) -> None:
+    _check(desc, rows=[(grad, "grad")], codes=codes, scales=scales)
     _raise(lib().aqsgd_grad_quant(ctypes.byref(desc), _dev(grad, "grad"), _dev(codes, "codes"),
                                   _dev(scales, "scales"), _stream(stream)))
 
 
 def grad_dequant(desc: Desc, codes, scales, out, stream=None) -> None:
+    _check(desc, rows=[(out, "out")], codes=codes, scales=scales)
     _raise(lib().aqsgd_grad_dequant(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
                                     _dev(out, "out"), _stream(stream)))
 
 
 def seed(desc: Desc, act, sample_ids, m_buf, stream=None) -> None:
     """``aqsgd_seed``: uncompressed first visit, ``m_buf[sample_ids] <- act``."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, m_buf=m_buf, stream=stream)
     _raise(lib().aqsgd_seed(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
                             _dev(m_buf, "m_buf"), _stream(stream)))
 
 
-def encode_seen(desc: Desc, act, sample_ids, m_buf, seen, first, codes, scales, stream=None) -> None:
-    """``aqsgd_encode_seen``: Algorithm 1's sender with the first-visit branch."""
+def _copy_desc(desc: Desc) -> Desc:
+    return Desc(desc.batch, desc.n_per, desc.n_samples, desc.bits, desc.group, desc.dtype, desc.rounding,
+                desc.rng_seed)
+
+
+def encode_job(desc: Desc, act, sample_ids, m_buf, codes, scales) -> Job:
+    """An ``aqsgd_encode`` call as one job of :func:`run_jobs` (the descriptor is copied)."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales)
+    return Job(JOB_ENCODE, _copy_desc(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
+               _dev(m_buf, "m_buf"), _dev(codes, "codes"), _dev(scales, "scales"), None)
+
+
+def decode_job(desc: Desc, codes, scales, sample_ids, m_buf, out) -> Job:
+    _check(desc, rows=[(out, "out")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales)
+    return Job(JOB_DECODE, _copy_desc(desc), None, _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"),
+               _dev(codes, "codes"), _dev(scales, "scales"), _dev(out, "out"))
+
+
+def grad_quant_job(desc: Desc, grad, codes, scales) -> Job:
+    _check(desc, rows=[(grad, "grad")], codes=codes, scales=scales)
+    return Job(JOB_GRAD_QUANT, _copy_desc(desc), _dev(grad, "grad"), None, None, _dev(codes, "codes"),
+               _dev(scales, "scales"), None)
+
+
+def grad_dequant_job(desc: Desc, codes, scales, out) -> Job:
+    _check(desc, rows=[(out, "out")], codes=codes, scales=scales)
+    return Job(JOB_GRAD_DEQUANT, _copy_desc(desc), None, None, None, _dev(codes, "codes"),
+               _dev(scales, "scales"), _dev(out, "out"))
+
+
+def run_jobs(jobs, stream=None) -> None:
+    """``aqsgd_run_jobs``: independent messages (built with the ``*_job`` helpers) in as few
+    launches as possible.  The tensors the jobs point at must stay alive until the stream
+    has run them, as for the single calls."""
+    arr = (Job * len(jobs))(*jobs)
+    _raise(lib().aqsgd_run_jobs(arr, len(jobs), _stream(stream)))
+
+
+def encode_seen(desc: Desc, act, sample_ids, m_buf, seen, stamp: int, first, codes, scales, stream=None) -> None:
+    """``aqsgd_encode_seen``: Algorithm 1's sender with the first-visit branch.  ``seen`` is an
+    int32 tensor (one 32-bit word per sample, zero = never visited); ``stamp`` a non-zero
+    32-bit number that no earlier call on this buffer has used."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales, stream=stream)
+    _want(seen, "seen", torch.int32, desc.n_samples, exact=True)
+    _want(first, "first", torch.int32, desc.batch, exact=True)
     _raise(lib().aqsgd_encode_seen(ctypes.byref(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
-                                   _dev(m_buf, "m_buf"), _dev(seen, "seen"), _dev(first, "first"),
-                                   _dev(codes, "codes"), _dev(scales, "scales"), _stream(stream)))
+                                   _dev(m_buf, "m_buf"), _dev(seen, "seen"), stamp & 0xFFFFFFFF,
+                                   _dev(first, "first"), _dev(codes, "codes"), _dev(scales, "scales"),
+                                   _stream(stream)))
 
 
-def decode_seen(desc: Desc, codes, scales, full, sample_ids, m_buf, seen, out, stream=None) -> None:
+def decode_seen(desc: Desc, codes, scales, full, sample_ids, m_buf, seen, stamp: int, out, stream=None) -> None:
     """``aqsgd_decode_seen``: Algorithm 1's receiver with the first-visit branch."""
+    _check(desc, rows=[(out, "out"), (full, "full")], ids=sample_ids, m_buf=m_buf, codes=codes,
+           scales=scales, stream=stream)
+    _want(seen, "seen", torch.int32, desc.n_samples, exact=True)
     _raise(lib().aqsgd_decode_seen(ctypes.byref(desc), _dev(codes, "codes"), _dev(scales, "scales"),
                                    _dev(full, "full"), _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"),
-                                   _dev(seen, "seen"), _dev(out, "out"), _stream(stream)))
+                                   _dev(seen, "seen"), stamp & 0xFFFFFFFF, _dev(out, "out"), _stream(stream)))
 
 
 def lowbit_row_bytes(desc: Desc, m_bits: int) -> int:
     return int(lib().aqsgd_lowbit_row_bytes(ctypes.byref(desc), m_bits))
 
 
+def _check_lowbit_store(desc: Desc, m_bits: int, m_codes, m_scales) -> None:
+    row = lowbit_row_bytes(desc, m_bits)
+    if row:                                     # 0: the library reports the bad descriptor
+        _want(m_codes, "m_codes", torch.uint8, desc.n_samples * row, exact=True)
+        _want(m_scales, "m_scales", torch.float32, desc.n_samples * (desc.n_per // desc.group), exact=True)
+
+
 def encode_lowbit(desc: Desc, m_bits: int, act, sample_ids, m_codes, m_scales, codes, scales,
                   stream=None) -> None:
     """``aqsgd_encode_lowbit``: sender with z-bit storage of the previous messages."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, codes=codes, scales=scales, stream=stream)
+    _check_lowbit_store(desc, m_bits, m_codes, m_scales)
     _raise(lib().aqsgd_encode_lowbit(ctypes.byref(desc), m_bits, _dev(act, "act"),
                                      _dev(sample_ids, "sample_ids"), _dev(m_codes, "m_codes"),
                                      _dev(m_scales, "m_scales"), _dev(codes, "codes"),
@@ -214,6 +336,8 @@ def encode_lowbit(desc: Desc, m_bits: int, act, sample_ids, m_codes, m_scales, c
 def decode_lowbit(desc: Desc, m_bits: int, codes, scales, sample_ids, m_codes, m_scales, out,
                   stream=None) -> None:
     """``aqsgd_decode_lowbit``: receiver with z-bit storage of the previous messages."""
+    _check(desc, rows=[(out, "out")], ids=sample_ids, codes=codes, scales=scales, stream=stream)
+    _check_lowbit_store(desc, m_bits, m_codes, m_scales)
     _raise(lib().aqsgd_decode_lowbit(ctypes.byref(desc), m_bits, _dev(codes, "codes"),
                                      _dev(scales, "scales"), _dev(sample_ids, "sample_ids"),
                                      _dev(m_codes, "m_codes"), _dev(m_scales, "m_scales"),
@@ -228,20 +352,36 @@ def topk_codes_bytes(desc: Desc, keep: int) -> int:
     return int(lib().aqsgd_topk_codes_bytes(ctypes.byref(desc), keep))
 
 
+def _check_topk(desc: Desc, keep: int, rows, what: str, bitmap, codes, scales) -> None:
+    nb = topk_bitmap_bytes(desc)
+    if nb:                                      # 0: the library reports the bad descriptor
+        _check(desc, rows=[(rows, what)], scales=scales)
+        _want(bitmap, "bitmap", torch.uint8, nb, exact=False)
+        nc = topk_codes_bytes(desc, keep)
+        if nc:
+            _want(codes, "codes", torch.uint8, nc, exact=False)
+
+
 def grad_topk_quant(desc: Desc, keep: int, grad, bitmap, codes, scales, stream=None) -> None:
     """``aqsgd_grad_topk_quant``: the ``keep`` largest entries per group, at 8 bits."""
+    _check_topk(desc, keep, grad, "grad", bitmap, codes, scales)
     _raise(lib().aqsgd_grad_topk_quant(ctypes.byref(desc), keep, _dev(grad, "grad"), _dev(bitmap, "bitmap"),
                                        _dev(codes, "codes"), _dev(scales, "scales"), _stream(stream)))
 
 
 def grad_topk_dequant(desc: Desc, keep: int, bitmap, codes, scales, out, stream=None) -> None:
     """``aqsgd_grad_topk_dequant``: kept entries reconstructed, the rest +0."""
+    _check_topk(desc, keep, out, "out", bitmap, codes, scales)
     _raise(lib().aqsgd_grad_topk_dequant(ctypes.byref(desc), keep, _dev(bitmap, "bitmap"),
                                          _dev(codes, "codes"), _dev(scales, "scales"), _dev(out, "out"),
                                          _stream(stream)))
 
 
 def check_ids(sample_ids, n_samples: int, flag, stream=None) -> None:
+    """``aqsgd_check_ids``: bit 0 of ``flag`` (one zeroed device int32) is set if an id is
+    out of range, bit 1 if two ids are equal."""
+    _want(sample_ids, "sample_ids", torch.int64, sample_ids.numel(), exact=True)
+    _want(flag, "flag", torch.int32, 1, exact=False)
     _raise(lib().aqsgd_check_ids(_dev(sample_ids, "sample_ids"), sample_ids.numel(), n_samples,
                                  _dev(flag, "flag"), _stream(stream)))
 

@@ -1,7 +1,9 @@
 // C ABI of the AQ-SGD boundary codec: argument checks and kernel dispatch.
 // See include/aqsgd.h for the contract of every entry point.
+#include <atomic>
 #include <cstdlib>
 #include <limits>
+#include <vector>
 
 #include "aqsgd_kernels.h"
 #include "aqsgd_lowbit.h"
@@ -12,39 +14,35 @@ namespace aqsgd {
 thread_local ProfileRequest g_profile_request = {nullptr, nullptr};
 
 // -- dtype fan-out (each dtype's kernels live in their own translation unit) ----
-hipError_t launch_quant_team(int dtype, int bits, int rounding, int shape, LaunchGeom g,
-                             const QuantArgs& a, hipStream_t s) {
+hipError_t launch_codec_jobs(int dtype, int bits, int rounding, int shape, const JobTable& t, hipStream_t s) {
     switch (dtype) {
-    case AQSGD_F32:  return launch_quant_team_dt<AQSGD_F32>(bits, rounding, shape, g, a, s);
-    case AQSGD_F16:  return launch_quant_team_dt<AQSGD_F16>(bits, rounding, shape, g, a, s);
-    case AQSGD_BF16: return launch_quant_team_dt<AQSGD_BF16>(bits, rounding, shape, g, a, s);
+    case AQSGD_F32:  return launch_codec_jobs_dt<AQSGD_F32>(bits, rounding, shape, t, s);
+    case AQSGD_F16:  return launch_codec_jobs_dt<AQSGD_F16>(bits, rounding, shape, t, s);
+    case AQSGD_BF16: return launch_codec_jobs_dt<AQSGD_BF16>(bits, rounding, shape, t, s);
     default:         return hipErrorInvalidValue;
     }
 }
-hipError_t launch_dequant_flat(int dtype, int bits, int unroll, LaunchGeom g, const DequantArgs& a,
-                               hipStream_t s) {
+hipError_t launch_dequant_jobs(int dtype, int unroll, const JobTable& t, hipStream_t s) {
     switch (dtype) {
-    case AQSGD_F32:  return launch_dequant_flat_dt<AQSGD_F32>(bits, unroll, g, a, s);
-    case AQSGD_F16:  return launch_dequant_flat_dt<AQSGD_F16>(bits, unroll, g, a, s);
-    case AQSGD_BF16: return launch_dequant_flat_dt<AQSGD_BF16>(bits, unroll, g, a, s);
+    case AQSGD_F32:  return launch_dequant_jobs_dt<AQSGD_F32>(unroll, t, s);
+    case AQSGD_F16:  return launch_dequant_jobs_dt<AQSGD_F16>(unroll, t, s);
+    case AQSGD_BF16: return launch_dequant_jobs_dt<AQSGD_BF16>(unroll, t, s);
     default:         return hipErrorInvalidValue;
     }
 }
-hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, LaunchGeom g, const QuantArgs& a,
-                                 hipStream_t s) {
+hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, const QuantJob& a, hipStream_t s) {
     switch (dtype) {
-    case AQSGD_F32:  return launch_quant_anyshape_dt<AQSGD_F32>(bits, rounding, g, a, s);
-    case AQSGD_F16:  return launch_quant_anyshape_dt<AQSGD_F16>(bits, rounding, g, a, s);
-    case AQSGD_BF16: return launch_quant_anyshape_dt<AQSGD_BF16>(bits, rounding, g, a, s);
+    case AQSGD_F32:  return launch_quant_anyshape_dt<AQSGD_F32>(bits, rounding, a, s);
+    case AQSGD_F16:  return launch_quant_anyshape_dt<AQSGD_F16>(bits, rounding, a, s);
+    case AQSGD_BF16: return launch_quant_anyshape_dt<AQSGD_BF16>(bits, rounding, a, s);
     default:         return hipErrorInvalidValue;
     }
 }
-hipError_t launch_dequant_anyshape(int dtype, int bits, LaunchGeom g, const DequantArgs& a,
-                                   hipStream_t s) {
+hipError_t launch_dequant_anyshape(int dtype, const DequantJob& a, hipStream_t s) {
     switch (dtype) {
-    case AQSGD_F32:  return launch_dequant_anyshape_dt<AQSGD_F32>(bits, g, a, s);
-    case AQSGD_F16:  return launch_dequant_anyshape_dt<AQSGD_F16>(bits, g, a, s);
-    case AQSGD_BF16: return launch_dequant_anyshape_dt<AQSGD_BF16>(bits, g, a, s);
+    case AQSGD_F32:  return launch_dequant_anyshape_dt<AQSGD_F32>(a, s);
+    case AQSGD_F16:  return launch_dequant_anyshape_dt<AQSGD_F16>(a, s);
+    case AQSGD_BF16: return launch_dequant_anyshape_dt<AQSGD_BF16>(a, s);
     default:         return hipErrorInvalidValue;
     }
 }
@@ -63,12 +61,9 @@ namespace {
 
 // Launch-shape knobs.  They change how the work is cut into workgroups, never a
 // result bit.  Defaults come from the environment, once, so a sweep needs no
-// rebuild; aqsgd_set_launch_shape overrides them for the process.
-struct Tuning {
-    int64_t max_blocks;      // upper bound on workgroups per launch
-    int dequant_unroll;      // chunks per lane and step in the dequantising kernel (1, 2, 4)
-};
-
+// rebuild; aqsgd_set_launch_shape overrides them for the process.  Each knob is
+// an atomic of its own: a call reads each one once, so a change made by another
+// thread takes effect for whole calls only.
 int env_int(const char* name, int fallback) {
     const char* v = std::getenv(name);
     if (!v || !*v) return fallback;
@@ -77,17 +72,19 @@ int env_int(const char* name, int fallback) {
     return (end && *end == '\0' && x > 0 && x < (1L << 30)) ? static_cast<int>(x) : fallback;
 }
 
-Tuning tuning_from_env() {
-    Tuning x;
-    x.max_blocks = env_int("AQSGD_MAX_BLOCKS", 1 << 20);
+int64_t env_max_blocks() { return env_int("AQSGD_MAX_BLOCKS", 1 << 20); }
+int env_dequant_unroll() {
     const int u = env_int("AQSGD_DEQUANT_UNROLL", 2);
-    x.dequant_unroll = (u == 1 || u == 2 || u == 4) ? u : 2;
-    return x;
+    return (u == 1 || u == 2 || u == 4) ? u : 2;
 }
 
-Tuning& tuning() {
-    static Tuning t = tuning_from_env();
-    return t;
+std::atomic<int64_t>& max_blocks_knob() {
+    static std::atomic<int64_t> v{env_max_blocks()};
+    return v;
+}
+std::atomic<int>& dequant_unroll_knob() {
+    static std::atomic<int> v{env_dequant_unroll()};
+    return v;
 }
 
 constexpr int64_t kMaxGridY = 65535;
@@ -137,82 +134,180 @@ int teams_per_block(int shape) {
     }
 }
 
-LaunchGeom geometry(int64_t units_per_sample, int64_t units_per_block, int64_t batch) {
+// Workgroups of one job: grid_y walks the samples, grid_x the pieces of a sample,
+// bounded by `max_blocks` in all (the kernels loop over what is left).
+LaunchGeom geometry(int64_t units_per_sample, int64_t units_per_block, int64_t batch, int64_t max_blocks) {
     LaunchGeom g;
     const int64_t gy = batch < kMaxGridY ? batch : kMaxGridY;
     int64_t gx = (units_per_sample + units_per_block - 1) / units_per_block;
-    const int64_t cap = tuning().max_blocks / gy > 0 ? tuning().max_blocks / gy : 1;
+    const int64_t cap = max_blocks / gy > 0 ? max_blocks / gy : 1;
     if (gx > cap) gx = cap;
     if (gx < 1) gx = 1;
-    g.grid_x = static_cast<unsigned>(gx);
-    g.grid_y = static_cast<unsigned>(gy);
+    g.grid_x = static_cast<uint32_t>(gx);
+    g.grid_y = static_cast<uint32_t>(gy);
     return g;
 }
 
-// Quantising side shared by aqsgd_encode and aqsgd_grad_quant.
-int run_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const void* src, const int64_t* ids,
-              void* m_buf, uint8_t* codes, float* scales, hipStream_t stream,
-              const uint8_t* seen = nullptr) {
-    QuantArgs a;
+int threads_of_shape(int shape) {
+    switch (shape) {
+    case kTeam1024x2: case kTeam1024x4: return 1024;
+    default: return kBlock;
+    }
+}
+
+// First-visit arguments of the *_seen entry points (all null / 0 otherwise).
+struct SeenArgs {
+    uint32_t* seen = nullptr;
+    int32_t* first = nullptr;
+    const void* full = nullptr;
+    uint32_t stamp = 0;
+};
+
+// One message as the kernels see it.  Quantising side: aqsgd_encode, aqsgd_grad_quant.
+struct QuantPlan {
+    QuantJob job;
+    int dtype, bits, rounding;
+    int shape;                 // team shape, or -1: any-shape kernel (launched on its own)
+};
+
+QuantPlan plan_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const void* src, const int64_t* ids,
+                     void* m_buf, uint8_t* codes, float* scales, const SeenArgs& sa = SeenArgs()) {
+    QuantPlan p;
+    QuantJob& a = p.job;
     a.src = src; a.ids = ids; a.m_buf = m_buf; a.codes = codes; a.scales = scales;
     a.n_per = n_per; a.gps = n_per / d->group;
     a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
-    a.seed = d->rng_seed; a.seen = seen;
-    hipError_t err;
-    if (d->group % kChunk == 0 && a.cpg <= kMaxTeamChunks) {
-        const int shape = team_shape_for(a.cpg);
-        err = launch_quant_team(d->dtype, d->bits, d->rounding, shape,
-                                geometry(a.gps, teams_per_block(shape), batch), a, stream);
-    } else {
-        err = launch_quant_anyshape(d->dtype, d->bits, d->rounding, geometry(a.gps, kBlock, batch), a,
-                                    stream);
-    }
-    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+    a.block0 = 0; a.grid_x = a.grid_y = 1;
+    a.seed = d->rng_seed; a.seen = sa.seen; a.first = sa.first; a.stamp = sa.stamp;
+    p.dtype = d->dtype; p.bits = d->bits; p.rounding = d->rounding;
+    p.shape = (d->group % kChunk == 0 && a.cpg <= kMaxTeamChunks) ? team_shape_for(a.cpg) : -1;
+    return p;
 }
 
-int run_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t* codes,
-                const float* scales, const int64_t* ids, void* m_buf, void* out, hipStream_t stream,
-                const uint8_t* seen = nullptr) {
-    DequantArgs a;
-    a.codes = codes; a.scales = scales; a.ids = ids; a.m_buf = m_buf; a.out = out;
+// Dequantising side: aqsgd_decode, aqsgd_grad_dequant.
+struct DequantPlan {
+    DequantJob job;
+    int dtype;
+    bool flat;                 // false: any-shape kernel (launched on its own)
+};
+
+DequantPlan plan_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const uint8_t* codes,
+                         const float* scales, const int64_t* ids, void* m_buf, void* out,
+                         const SeenArgs& sa = SeenArgs()) {
+    DequantPlan p;
+    DequantJob& a = p.job;
+    a.codes = codes; a.scales = scales; a.ids = ids; a.m_buf = m_buf; a.out = out; a.full = sa.full;
     a.n_per = n_per; a.gps = n_per / d->group; a.cps = n_per / kChunk;
-    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
-    a.seen = seen;
-    hipError_t err;
-    if (d->group % kChunk == 0) {
-        const int unroll = tuning().dequant_unroll;
-        err = launch_dequant_flat(d->dtype, d->bits, unroll,
-                                  geometry(a.cps, static_cast<int64_t>(kBlock) * unroll, batch), a, stream);
-    } else {
-        err = launch_dequant_anyshape(d->dtype, d->bits, geometry(a.gps, kBlock, batch), a, stream);
+    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk; a.bits = d->bits;
+    a.block0 = 0; a.grid_x = a.grid_y = 1;
+    a.seen = sa.seen; a.stamp = sa.stamp;
+    p.dtype = d->dtype;
+    p.flat = d->group % kChunk == 0;
+    return p;
+}
+
+// The launches of a set of independent messages: quantising jobs that share dtype, bit
+// width, rounding mode and team shape go into one grid, together with the dequantising
+// jobs of that dtype that are still waiting; dequantising jobs without such a host get a
+// grid of their own; jobs that need the any-shape kernels are launched one by one.
+int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipStream_t stream) {
+    const int64_t max_blocks = max_blocks_knob().load(std::memory_order_relaxed);
+    const int unroll = dequant_unroll_knob().load(std::memory_order_relaxed);
+    std::vector<bool> q_done(qs.size(), false), d_done(ds.size(), false);
+    hipError_t err = hipSuccess;
+
+    auto add_dequant = [&](JobTable& t, int dtype, int threads, int job_unroll, int64_t& blocks) {
+        for (size_t k = 0; k < ds.size() && t.n_dequant < kMaxDequantJobs; ++k) {
+            if (d_done[k] || !ds[k].flat || ds[k].dtype != dtype) continue;
+            DequantJob a = ds[k].job;
+            const LaunchGeom g = geometry(a.cps, static_cast<int64_t>(threads) * job_unroll, a.batch, max_blocks);
+            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.block0 = static_cast<uint32_t>(blocks);
+            blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
+            t.d[t.n_dequant++] = a;
+            d_done[k] = true;
+        }
+    };
+
+    for (size_t i = 0; i < qs.size() && err == hipSuccess; ++i) {
+        if (q_done[i]) continue;
+        QuantPlan& lead = qs[i];
+        if (lead.shape < 0) {                            // any-shape kernel, on its own
+            const LaunchGeom g = geometry(lead.job.gps, kBlock, lead.job.batch, max_blocks);
+            lead.job.grid_x = g.grid_x; lead.job.grid_y = g.grid_y;
+            err = launch_quant_anyshape(lead.dtype, lead.bits, lead.rounding, lead.job, stream);
+            q_done[i] = true;
+            continue;
+        }
+        JobTable t;
+        t.n_quant = t.n_dequant = 0;
+        int64_t blocks = 0;
+        for (size_t k = i; k < qs.size() && t.n_quant < kMaxQuantJobs; ++k) {
+            const QuantPlan& c = qs[k];
+            if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.bits != lead.bits ||
+                c.rounding != lead.rounding)
+                continue;
+            QuantJob a = c.job;
+            const LaunchGeom g = geometry(a.gps, teams_per_block(c.shape), a.batch, max_blocks);
+            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.block0 = static_cast<uint32_t>(blocks);
+            blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
+            t.q[t.n_quant++] = a;
+            q_done[k] = true;
+        }
+        t.dequant_block0 = static_cast<uint32_t>(blocks);
+        add_dequant(t, lead.dtype, threads_of_shape(lead.shape), kHostedDequantUnroll, blocks);
+        t.total_blocks = static_cast<uint32_t>(blocks);
+        err = launch_codec_jobs(lead.dtype, lead.bits, lead.rounding, lead.shape, t, stream);
+    }
+    for (size_t i = 0; i < ds.size() && err == hipSuccess; ++i) {
+        if (d_done[i]) continue;
+        if (!ds[i].flat) {
+            DequantJob& a = ds[i].job;
+            const LaunchGeom g = geometry(a.gps, kBlock, a.batch, max_blocks);
+            a.grid_x = g.grid_x; a.grid_y = g.grid_y;
+            err = launch_dequant_anyshape(ds[i].dtype, a, stream);
+            d_done[i] = true;
+            continue;
+        }
+        JobTable t;
+        t.n_quant = t.n_dequant = 0;
+        t.dequant_block0 = 0;
+        int64_t blocks = 0;
+        add_dequant(t, ds[i].dtype, kBlock, unroll, blocks);
+        t.total_blocks = static_cast<uint32_t>(blocks);
+        err = launch_dequant_jobs(ds[i].dtype, unroll, t, stream);
     }
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
-// Row copy for the uncompressed first visit: m_buf[ids[i]] <- act[i], and out[i] <- act[i]
-// when `out` is given.  With `seen`, only samples that have no previous message yet
-// (seen[id] == 0) are copied.  V = 16 bytes per lane and step (streaming accesses) when
-// the row size allows it, else one element.
+int launch_one(const QuantPlan& q, hipStream_t stream) {
+    std::vector<QuantPlan> qs(1, q);
+    std::vector<DequantPlan> ds;
+    return launch_plans(qs, ds, stream);
+}
+
+int launch_one(const DequantPlan& d, hipStream_t stream) {
+    std::vector<QuantPlan> qs;
+    std::vector<DequantPlan> ds(1, d);
+    return launch_plans(qs, ds, stream);
+}
+
+// Row copy for the uncompressed first visit of aqsgd_seed: m_buf[ids[i]] <- act[i].
+// V = 16 bytes per lane and step (streaming accesses) when the row size allows it,
+// else one element.
 template <typename V>
 __global__ __launch_bounds__(kBlock)
-void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, V* out, const uint8_t* seen,
-                      int64_t units_per_row, int batch) {
+void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, int64_t units_per_row, int batch) {
     for (int i = blockIdx.y; i < batch; i += gridDim.y) {
         const int64_t row = ids[i];
-        if (seen != nullptr && seen[row] != 0) continue;
         const V* src = act + static_cast<int64_t>(i) * units_per_row;
         V* dst = m_buf + row * units_per_row;
-        V* dst2 = out ? out + static_cast<int64_t>(i) * units_per_row : nullptr;
         for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < units_per_row;
              c += static_cast<int64_t>(gridDim.x) * kBlock) {
             if constexpr (sizeof(V) == 16) {
                 const V v = __builtin_nontemporal_load(src + c);
                 __builtin_nontemporal_store(v, dst + c);
-                if (dst2) __builtin_nontemporal_store(v, dst2 + c);
             } else {
-                const V v = src[c];
-                dst[c] = v;
-                if (dst2) dst2[c] = v;
+                dst[c] = src[c];
             }
         }
     }
@@ -220,37 +315,74 @@ void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, V* out, const 
 
 template <typename V>
 hipError_t launch_seed_rows_as(const aqsgd_desc* d, int64_t row_bytes, const void* act, const int64_t* ids,
-                               void* m_buf, void* out, const uint8_t* seen, hipStream_t s) {
+                               void* m_buf, hipStream_t s) {
     const int64_t units = row_bytes / static_cast<int64_t>(sizeof(V));
-    const LaunchGeom g = geometry(units, static_cast<int64_t>(kBlock) * (sizeof(V) == 16 ? 2 : 4), d->batch);
+    const LaunchGeom g = geometry(units, static_cast<int64_t>(kBlock) * (sizeof(V) == 16 ? 2 : 4), d->batch,
+                            max_blocks_knob().load(std::memory_order_relaxed));
     return launch_kernel(seed_rows_kernel<V>, dim3(g.grid_x, g.grid_y), dim3(kBlock), s,
-                         static_cast<const V*>(act), ids, static_cast<V*>(m_buf), static_cast<V*>(out), seen,
-                         units, static_cast<int>(d->batch));
+                         static_cast<const V*>(act), ids, static_cast<V*>(m_buf), units,
+                         static_cast<int>(d->batch));
 }
 
-hipError_t launch_seed_rows(const aqsgd_desc* d, const void* act, const int64_t* ids, void* m_buf, void* out,
-                            const uint8_t* seen, hipStream_t s) {
+hipError_t launch_seed_rows(const aqsgd_desc* d, const void* act, const int64_t* ids, void* m_buf,
+                            hipStream_t s) {
     const int64_t eb = d->dtype == AQSGD_F32 ? 4 : 2;
     const int64_t row_bytes = d->n_per * eb;
-    if (row_bytes % 16 == 0) return launch_seed_rows_as<u32x4_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
-    if (eb == 4) return launch_seed_rows_as<uint32_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
-    return launch_seed_rows_as<uint16_t>(d, row_bytes, act, ids, m_buf, out, seen, s);
+    if (row_bytes % 16 == 0) return launch_seed_rows_as<u32x4_t>(d, row_bytes, act, ids, m_buf, s);
+    if (eb == 4) return launch_seed_rows_as<uint32_t>(d, row_bytes, act, ids, m_buf, s);
+    return launch_seed_rows_as<uint16_t>(d, row_bytes, act, ids, m_buf, s);
 }
 
-// After a call with first-visit handling: note which samples were new, then mark them all.
-__global__ void mark_seen_kernel(const int64_t* ids, int batch, uint8_t* seen, int32_t* first) {
-    for (int i = blockIdx.x * blockDim.x + threadIdx.x; i < batch; i += gridDim.x * blockDim.x) {
-        const int64_t row = ids[i];
-        if (first) first[i] = seen[row] == 0;
-        seen[row] = 1;
-    }
+int check_encode(const aqsgd_desc* d, const void* act, const int64_t* ids, const void* m_buf,
+                 const uint8_t* codes, const float* scales) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    if (!act || !ids || !m_buf || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return AQSGD_OK;
 }
 
-hipError_t launch_mark_seen(const aqsgd_desc* d, const int64_t* ids, uint8_t* seen, int32_t* first,
-                            hipStream_t s) {
-    const unsigned blocks = static_cast<unsigned>((d->batch + kBlock - 1) / kBlock);
-    return launch_kernel(mark_seen_kernel, dim3(blocks < 1024 ? blocks : 1024), dim3(kBlock), s, ids,
-                         static_cast<int>(d->batch), seen, first);
+int check_decode(const aqsgd_desc* d, const uint8_t* codes, const float* scales, const int64_t* ids,
+                 const void* m_buf, const void* out) {
+    const int rc = check_desc(d, true);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    if (!codes || !scales || !ids || !m_buf || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
+        !aligned(ids, 8))
+        return AQSGD_ERR_ALIGN;
+    return AQSGD_OK;
+}
+
+int check_grad_quant(const aqsgd_desc* d, const void* grad, const uint8_t* codes, const float* scales) {
+    const int rc = check_desc(d, false);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    if (!grad || !codes || !scales) return AQSGD_ERR_NULL;
+    if (!aligned(grad, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
+    return AQSGD_OK;
+}
+
+int check_grad_dequant(const aqsgd_desc* d, const uint8_t* codes, const float* scales, const void* out) {
+    const int rc = check_desc(d, false);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    if (!codes || !scales || !out) return AQSGD_ERR_NULL;
+    if (!aligned(out, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
+    return AQSGD_OK;
+}
+
+// The backward message has no per-sample rows to gather, and n_per is a multiple of
+// the group, so the call tensor is treated as one long sample.
+QuantPlan plan_grad_quant(const aqsgd_desc* d, const void* grad, uint8_t* codes, float* scales) {
+    const int64_t n = d->batch * d->n_per;
+    const bool flat = n <= (int64_t{1} << 34);
+    return plan_quant(d, flat ? 1 : d->batch, flat ? n : d->n_per, grad, nullptr, nullptr, codes, scales);
+}
+
+DequantPlan plan_grad_dequant(const aqsgd_desc* d, const uint8_t* codes, const float* scales, void* out) {
+    const int64_t n = d->batch * d->n_per;
+    const bool flat = n <= (int64_t{1} << 34);
+    return plan_dequant(d, flat ? 1 : d->batch, flat ? n : d->n_per, codes, scales, nullptr, nullptr, out);
 }
 
 int lowbit_shape_for(int cpg) {
@@ -294,7 +426,9 @@ int run_lowbit(const aqsgd_desc* d, int32_t m_bits, bool sender, const void* act
     a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
     const int shape = lowbit_shape_for(a.cpg);
     const hipError_t err = launch_lowbit(d->dtype, d->bits, m_bits, shape, sender,
-                                         geometry(a.gps, lowbit_teams_per_block(shape), d->batch), a, stream);
+                                         geometry(a.gps, lowbit_teams_per_block(shape), d->batch,
+                                                  max_blocks_knob().load(std::memory_order_relaxed)),
+                                         a, stream);
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
@@ -315,7 +449,8 @@ int run_topk(const aqsgd_desc* d, int32_t keep, bool sender, const void* grad, v
     a.group = d->group; a.cpg = d->group / kChunk; a.keep = keep;
     a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
     const int cpl = a.cpg <= kWave ? 1 : (a.cpg <= 2 * kWave ? 2 : 4);
-    const LaunchGeom g = geometry(a.n_groups, kBlock / kWave, 1);
+    const LaunchGeom g = geometry(a.n_groups, kBlock / kWave, 1,
+                                  max_blocks_knob().load(std::memory_order_relaxed));
     const hipError_t err = launch_topk(d->dtype, cpl, sender, g.grid_x, a, stream);
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
@@ -351,56 +486,69 @@ size_t aqsgd_scales_count(const aqsgd_desc* d) {
 
 int aqsgd_encode(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
                  uint8_t* codes, float* scales, void* stream) {
-    const int rc = check_desc(d, true);
-    if (rc != AQSGD_OK) return rc;
-    if (d->batch == 0) return AQSGD_OK;
-    if (!act || !sample_ids || !m_buf || !codes || !scales) return AQSGD_ERR_NULL;
-    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
-        !aligned(sample_ids, 8))
-        return AQSGD_ERR_ALIGN;
-    return run_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales,
-                     static_cast<hipStream_t>(stream));
+    const int rc = check_encode(d, act, sample_ids, m_buf, codes, scales);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    return launch_one(plan_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales),
+                      static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_decode(const aqsgd_desc* d, const uint8_t* codes, const float* scales,
                  const int64_t* sample_ids, void* m_buf, void* out, void* stream) {
-    const int rc = check_desc(d, true);
-    if (rc != AQSGD_OK) return rc;
-    if (d->batch == 0) return AQSGD_OK;
-    if (!codes || !scales || !sample_ids || !m_buf || !out) return AQSGD_ERR_NULL;
-    if (!aligned(out, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
-        !aligned(sample_ids, 8))
-        return AQSGD_ERR_ALIGN;
-    return run_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out,
-                       static_cast<hipStream_t>(stream));
+    const int rc = check_decode(d, codes, scales, sample_ids, m_buf, out);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    return launch_one(plan_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out),
+                      static_cast<hipStream_t>(stream));
 }
 
-// The backward message has no per-sample rows to gather, and n_per is a
-// multiple of the group, so the call tensor is treated as one long sample.
 int aqsgd_grad_quant(const aqsgd_desc* d, const void* grad, uint8_t* codes, float* scales,
                      void* stream) {
-    const int rc = check_desc(d, false);
-    if (rc != AQSGD_OK) return rc;
-    if (d->batch == 0) return AQSGD_OK;
-    if (!grad || !codes || !scales) return AQSGD_ERR_NULL;
-    if (!aligned(grad, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
-    const int64_t n = d->batch * d->n_per;
-    const bool flat = n <= (int64_t{1} << 34);
-    return run_quant(d, flat ? 1 : d->batch, flat ? n : d->n_per, grad, nullptr, nullptr, codes, scales,
-                     static_cast<hipStream_t>(stream));
+    const int rc = check_grad_quant(d, grad, codes, scales);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    return launch_one(plan_grad_quant(d, grad, codes, scales), static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_grad_dequant(const aqsgd_desc* d, const uint8_t* codes, const float* scales, void* out,
                        void* stream) {
-    const int rc = check_desc(d, false);
-    if (rc != AQSGD_OK) return rc;
-    if (d->batch == 0) return AQSGD_OK;
-    if (!codes || !scales || !out) return AQSGD_ERR_NULL;
-    if (!aligned(out, 16) || !aligned(codes, 16) || !aligned(scales, 4)) return AQSGD_ERR_ALIGN;
-    const int64_t n = d->batch * d->n_per;
-    const bool flat = n <= (int64_t{1} << 34);
-    return run_dequant(d, flat ? 1 : d->batch, flat ? n : d->n_per, codes, scales, nullptr, nullptr, out,
-                       static_cast<hipStream_t>(stream));
+    const int rc = check_grad_dequant(d, codes, scales, out);
+    if (rc != AQSGD_OK || d->batch == 0) return rc;
+    return launch_one(plan_grad_dequant(d, codes, scales, out), static_cast<hipStream_t>(stream));
+}
+
+int aqsgd_run_jobs(const aqsgd_job* jobs, int32_t n_jobs, void* stream) {
+    if (n_jobs < 0) return AQSGD_ERR_SHAPE;
+    if (n_jobs == 0) return AQSGD_OK;
+    if (!jobs) return AQSGD_ERR_NULL;
+    std::vector<QuantPlan> qs;
+    std::vector<DequantPlan> ds;
+    for (int32_t k = 0; k < n_jobs; ++k) {               // every job is checked before anything is enqueued
+        const aqsgd_job& j = jobs[k];
+        const aqsgd_desc* d = &j.desc;
+        int rc;
+        switch (j.kind) {
+        case AQSGD_JOB_ENCODE:
+            rc = check_encode(d, j.src, j.sample_ids, j.m_buf, j.codes, j.scales);
+            if (rc == AQSGD_OK && d->batch > 0)
+                qs.push_back(plan_quant(d, d->batch, d->n_per, j.src, j.sample_ids, j.m_buf, j.codes, j.scales));
+            break;
+        case AQSGD_JOB_DECODE:
+            rc = check_decode(d, j.codes, j.scales, j.sample_ids, j.m_buf, j.out);
+            if (rc == AQSGD_OK && d->batch > 0)
+                ds.push_back(plan_dequant(d, d->batch, d->n_per, j.codes, j.scales, j.sample_ids, j.m_buf, j.out));
+            break;
+        case AQSGD_JOB_GRAD_QUANT:
+            rc = check_grad_quant(d, j.src, j.codes, j.scales);
+            if (rc == AQSGD_OK && d->batch > 0) qs.push_back(plan_grad_quant(d, j.src, j.codes, j.scales));
+            break;
+        case AQSGD_JOB_GRAD_DEQUANT:
+            rc = check_grad_dequant(d, j.codes, j.scales, j.out);
+            if (rc == AQSGD_OK && d->batch > 0) ds.push_back(plan_grad_dequant(d, j.codes, j.scales, j.out));
+            break;
+        default:
+            rc = AQSGD_ERR_SHAPE;
+        }
+        if (rc != AQSGD_OK) return rc;
+    }
+    return launch_plans(qs, ds, static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_seed(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
@@ -410,42 +558,38 @@ int aqsgd_seed(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, 
     if (d->batch == 0) return AQSGD_OK;
     if (!act || !sample_ids || !m_buf) return AQSGD_ERR_NULL;
     if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(sample_ids, 8)) return AQSGD_ERR_ALIGN;
-    const hipError_t err = launch_seed_rows(d, act, sample_ids, m_buf, nullptr, nullptr,
-                                            static_cast<hipStream_t>(stream));
+    const hipError_t err = launch_seed_rows(d, act, sample_ids, m_buf, static_cast<hipStream_t>(stream));
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
 int aqsgd_encode_seen(const aqsgd_desc* d, const void* act, const int64_t* sample_ids, void* m_buf,
-                      uint8_t* seen, int32_t* first, uint8_t* codes, float* scales, void* stream) {
-    const int rc = check_desc(d, true);
+                      uint32_t* seen, uint32_t stamp, int32_t* first, uint8_t* codes, float* scales,
+                      void* stream) {
+    const int rc = check_encode(d, act, sample_ids, m_buf, codes, scales);
     if (rc != AQSGD_OK) return rc;
+    if (stamp == 0) return AQSGD_ERR_SHAPE;
     if (d->batch == 0) return AQSGD_OK;
-    if (!act || !sample_ids || !m_buf || !seen || !first || !codes || !scales) return AQSGD_ERR_NULL;
-    if (!aligned(act, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
-        !aligned(sample_ids, 8) || !aligned(first, 4))
-        return AQSGD_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    // the three launches read `seen` as it was before the call; only the last one writes it
-    int st = run_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales, s, seen);
-    if (st != AQSGD_OK) return st;
-    if (launch_seed_rows(d, act, sample_ids, m_buf, nullptr, seen, s) != hipSuccess) return AQSGD_ERR_LAUNCH;
-    return launch_mark_seen(d, sample_ids, seen, first, s) == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+    if (!seen || !first) return AQSGD_ERR_NULL;
+    if (!aligned(first, 4) || !aligned(seen, 4)) return AQSGD_ERR_ALIGN;
+    SeenArgs sa;
+    sa.seen = seen; sa.first = first; sa.stamp = stamp;
+    return launch_one(plan_quant(d, d->batch, d->n_per, act, sample_ids, m_buf, codes, scales, sa),
+                      static_cast<hipStream_t>(stream));
 }
 
 int aqsgd_decode_seen(const aqsgd_desc* d, const uint8_t* codes, const float* scales, const void* full,
-                      const int64_t* sample_ids, void* m_buf, uint8_t* seen, void* out, void* stream) {
-    const int rc = check_desc(d, true);
+                      const int64_t* sample_ids, void* m_buf, uint32_t* seen, uint32_t stamp, void* out,
+                      void* stream) {
+    const int rc = check_decode(d, codes, scales, sample_ids, m_buf, out);
     if (rc != AQSGD_OK) return rc;
+    if (stamp == 0) return AQSGD_ERR_SHAPE;
     if (d->batch == 0) return AQSGD_OK;
-    if (!codes || !scales || !full || !sample_ids || !m_buf || !seen || !out) return AQSGD_ERR_NULL;
-    if (!aligned(out, 16) || !aligned(m_buf, 16) || !aligned(codes, 16) || !aligned(scales, 4) ||
-        !aligned(sample_ids, 8) || !aligned(full, 16))
-        return AQSGD_ERR_ALIGN;
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    int st = run_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out, s, seen);
-    if (st != AQSGD_OK) return st;
-    if (launch_seed_rows(d, full, sample_ids, m_buf, out, seen, s) != hipSuccess) return AQSGD_ERR_LAUNCH;
-    return launch_mark_seen(d, sample_ids, seen, nullptr, s) == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+    if (!seen || !full) return AQSGD_ERR_NULL;
+    if (!aligned(full, 16) || !aligned(seen, 4)) return AQSGD_ERR_ALIGN;
+    SeenArgs sa;
+    sa.seen = seen; sa.full = full; sa.stamp = stamp;
+    return launch_one(plan_dequant(d, d->batch, d->n_per, codes, scales, sample_ids, m_buf, out, sa),
+                      static_cast<hipStream_t>(stream));
 }
 
 size_t aqsgd_lowbit_row_bytes(const aqsgd_desc* d, int32_t m_bits) {
@@ -520,18 +664,19 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
     if (!sample_ids || !flag) return AQSGD_ERR_NULL;
     if (!aligned(sample_ids, 8) || !aligned(flag, 4)) return AQSGD_ERR_ALIGN;
     const int64_t blocks = (batch + kBlock - 1) / kBlock;
-    hipLaunchKernelGGL(check_ids_kernel, dim3(static_cast<unsigned>(blocks < 1024 ? blocks : 1024)),
-                       dim3(kBlock), 0, static_cast<hipStream_t>(stream), sample_ids, batch, n_samples, flag);
-    return hipGetLastError() == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
+    const hipError_t err = launch_kernel(check_ids_kernel, dim3(static_cast<unsigned>(blocks < 1024 ? blocks : 1024)),
+                                         dim3(kBlock), static_cast<hipStream_t>(stream), sample_ids, batch,
+                                         n_samples, flag);
+    return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;
 }
 
 int aqsgd_set_launch_shape(int64_t max_blocks, int32_t dequant_unroll) {
     if (max_blocks < 0 || max_blocks >= (int64_t{1} << 30)) return AQSGD_ERR_SHAPE;
     if (dequant_unroll != 0 && dequant_unroll != 1 && dequant_unroll != 2 && dequant_unroll != 4)
         return AQSGD_ERR_SHAPE;
-    const Tuning env = tuning_from_env();
-    tuning().max_blocks = max_blocks ? max_blocks : env.max_blocks;
-    tuning().dequant_unroll = dequant_unroll ? dequant_unroll : env.dequant_unroll;
+    max_blocks_knob().store(max_blocks ? max_blocks : env_max_blocks(), std::memory_order_relaxed);
+    dequant_unroll_knob().store(dequant_unroll ? dequant_unroll : env_dequant_unroll(),
+                                std::memory_order_relaxed);
     return AQSGD_OK;
 }
 

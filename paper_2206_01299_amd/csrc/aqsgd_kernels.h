@@ -13,8 +13,17 @@
 //   TEAM  > 64: the team is a whole workgroup; wave maxima meet in LDS.
 // Dequantising side (decode, grad_dequant): no reduction, one chunk per lane
 // and step, flat over the sample.
-// gridDim.y walks the samples of the call, gridDim.x the groups (or chunks)
-// inside a sample, so no index needs a 64-bit division on the device.
+//
+// One launch carries a table of independent jobs (messages): the quantising
+// jobs of one kernel configuration and any number of dequantising jobs.  A
+// stage of a pipeline has both kinds to do at the same time (the sending stage
+// encodes activations and reconstructs gradients, the receiving stage decodes
+// activations and quantises gradients), and a launch of a few tens of MB spends
+// a quarter of its time filling and draining the chip, so messages that are
+// ready together go out as one grid.  Workgroup b of the grid finds its job from
+// the jobs' first-workgroup numbers; inside a job the workgroups form a
+// grid_x x grid_y rectangle, grid_y walking the samples of the call and grid_x
+// the groups (or chunks) inside a sample, so no index needs a 64-bit division.
 #pragma once
 
 #include <hip/hip_ext.h>
@@ -31,7 +40,15 @@ void fill_arg_pointers(Tuple& t, void** argv, std::index_sequence<I...>) {
     ((argv[I] = static_cast<void*>(&std::get<I>(t))), ...);
 }
 
-struct QuantArgs {
+// First-visit handling (Algorithm 1's branch for a sample without a previous
+// message).  `seen` holds one 32-bit word per sample: 0 = never visited, else the
+// stamp of the call that visited it first.  A call carries its own stamp, which no
+// earlier call on this buffer used; a sample is new to the call if its word is 0
+// or equal to the call's stamp.  The second case lets the workgroup that owns the
+// sample's first piece write the stamp while other workgroups of the same launch
+// still read the word: both values mean "new" to them, and to every later call
+// the stamp means "seen".
+struct QuantJob {
     const void* src;           // act or grad  [batch, n_per]
     const int64_t* ids;        // sample ids, or nullptr (src rows are not gathered)
     void* m_buf;               // previous messages, or nullptr (direct quantisation)
@@ -42,24 +59,50 @@ struct QuantArgs {
     int32_t batch;
     int32_t group;             // G
     int32_t cpg;               // chunks per group (G / 8), team kernels only
+    uint32_t block0;           // first workgroup of this job in the launch
+    uint32_t grid_x, grid_y;   // its workgroups: grid_x per sample row, grid_y rows
     uint64_t seed;
-    const uint8_t* seen;       // or nullptr; else samples with seen[id] == 0 are skipped
+    uint32_t* seen;            // or nullptr: no first-visit handling
+    int32_t* first;            // with seen: first[i] = 1 if sample i was new, else 0
+    uint32_t stamp;            // with seen: this call's stamp (non-zero)
 };
 
-struct DequantArgs {
+struct DequantJob {
     const uint8_t* codes;
     const float* scales;
     const int64_t* ids;        // or nullptr
     void* m_buf;               // or nullptr: out = Q^-1 alone
     void* out;
+    const void* full;          // with seen: uncompressed rows of the call's new samples
     int64_t n_per;
     int64_t gps;
     int64_t cps;               // chunks per sample
     int32_t batch;
     int32_t group;
     int32_t cpg;
-    const uint8_t* seen;       // or nullptr; else samples with seen[id] == 0 are skipped
+    int32_t bits;
+    uint32_t block0;
+    uint32_t grid_x, grid_y;
+    uint32_t* seen;            // or nullptr
+    uint32_t stamp;
 };
+
+constexpr int kMaxQuantJobs = 8;       // per launch
+constexpr int kMaxDequantJobs = 8;
+
+struct JobTable {
+    int32_t n_quant, n_dequant;
+    uint32_t dequant_block0;           // workgroups below this number belong to quantising jobs
+    uint32_t total_blocks;
+    QuantJob q[kMaxQuantJobs];
+    DequantJob d[kMaxDequantJobs];
+};
+
+// Is sample `row` new to this call?  (see above; uniform over the workgroup)
+__device__ __forceinline__ bool first_visit(const uint32_t* seen, int64_t row, uint32_t stamp) {
+    const uint32_t w = seen[row];
+    return w == 0u || w == stamp;
+}
 
 constexpr int kBlock = 256;
 
@@ -74,7 +117,7 @@ constexpr int kBlock = 256;
 // the sample (ragged last step) is switched off, as a whole.
 // ---------------------------------------------------------------------------
 template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
-__device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char* src_s, char* m_s,
+__device__ __forceinline__ void quant_team_group(const QuantJob& a, const char* src_s, char* m_s,
                                                  uint8_t* codes_s, float* scales_s, int64_t src0,
                                                  int64_t g, const uint32_t (&cc)[CPL],
                                                  const uint32_t (&ua)[CPL], const uint32_t (&ub)[CPL],
@@ -176,8 +219,38 @@ __device__ __forceinline__ void quant_team_group(const QuantArgs& a, const char*
     if (lane_in_team == 0) scales_s[g] = sc.s_tx;
 }
 
+// First visit of a sample on the sender: the team's chunks of the group go from act
+// to m unchanged (the activation itself is the message).  Same chunk ownership and
+// clamping as above, so the two paths write a row with the same access pattern.
+template <int DT, int BITS, int TEAM, int CPL>
+__device__ __forceinline__ void copy_team_group(const QuantJob& a, const char* src_s, char* m_s, int64_t g,
+                                                const uint32_t (&cc)[CPL], const uint32_t (&ua)[CPL],
+                                                const uint32_t (&ub)[CPL]) {
+    constexpr int kEB = ElemBytes<DT>::value;
+    constexpr int kChunkBytes = kChunk * kEB;
+    constexpr int kUnitBytes = kUnit * kEB;
+    constexpr bool kUnits = UnitLayout<DT, BITS>::value;
+    const int64_t goff = g * a.group;
+    Raw<DT> ra[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        if constexpr (kUnits)
+            ra[k] = load_raw_units(src_s + goff * kEB + ua[k] * kUnitBytes, src_s + goff * kEB + ub[k] * kUnitBytes);
+        else
+            ra[k] = load_raw_at<DT>(src_s + goff * kEB + cc[k] * kChunkBytes);
+    }
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        if constexpr (kUnits)
+            store_raw_units(m_s + goff * kEB + ua[k] * kUnitBytes, m_s + goff * kEB + ub[k] * kUnitBytes, ra[k]);
+        else
+            store_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes, ra[k]);
+    }
+}
+
+// Workgroup (bx, by) of a quantising job's grid_x x grid_y rectangle.
 template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
-__device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_max) {
+__device__ __forceinline__ void quant_team_body(const QuantJob& a, uint32_t bx, uint32_t by, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
     constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
@@ -204,59 +277,80 @@ __device__ __forceinline__ void quant_team_body(const QuantArgs& a, float* wave_
         ub[k] = static_cast<uint32_t>(min((2 * k + 1) * TEAM + lane_in_team, 2 * a.cpg - 1));
     }
 
-    for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
+    for (int i = by; i < a.batch; i += a.grid_y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
-        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;      // flat offset of sample i
         const char* src_s = static_cast<const char*>(a.src) + src0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
         uint8_t* codes_s = a.codes + src0 / kChunk * BITS;
         float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
-        for (int64_t gbase = static_cast<int64_t>(blockIdx.x) * kTeamsPerBlock; gbase < a.gps;
-             gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
+        bool fresh = false;
+        if constexpr (HAS_BUF) {
+            if (a.seen != nullptr) {
+                fresh = __builtin_amdgcn_readfirstlane(first_visit(a.seen, row, a.stamp) ? 1 : 0) != 0;
+                if (bx == 0 && threadIdx.x == 0) {       // one writer per sample
+                    a.first[i] = fresh ? 1 : 0;
+                    if (fresh) a.seen[row] = a.stamp;
+                }
+            }
+        }
+
+        for (int64_t gbase = static_cast<int64_t>(bx) * kTeamsPerBlock; gbase < a.gps;
+             gbase += static_cast<int64_t>(a.grid_x) * kTeamsPerBlock) {
             const int64_t g = gbase + team;              // uniform over the team
-            if (g < a.gps)
-                quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF>(a, src_s, m_s, codes_s, scales_s,
-                                                                      src0, g, cc, ua, ub, lane_in_team,
-                                                                      wave_max);
+            if (g >= a.gps) continue;
+            if constexpr (HAS_BUF) {
+                if (fresh) {                             // uniform over the workgroup
+                    copy_team_group<DT, BITS, TEAM, CPL>(a, src_s, m_s, g, cc, ua, ub);
+                    continue;
+                }
+            }
+            quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF>(a, src_s, m_s, codes_s, scales_s, src0, g,
+                                                                  cc, ua, ub, lane_in_team, wave_max);
         }
     }
 }
 
-template <int DT, int BITS, int ROUND, int TEAM, int CPL>
-__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
-void quant_team_kernel(const QuantArgs a) {
-    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
-    static_assert(TEAM <= kWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
-    [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
-    if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, wave_max);
-    else quant_team_body<DT, BITS, ROUND, TEAM, CPL, false>(a, wave_max);
-}
-
 // ---------------------------------------------------------------------------
-// decode / grad_dequant, flat chunk kernel: UNROLL chunks per lane and step, all
+// decode / grad_dequant, flat chunk body: UNROLL chunks per lane and step, all
 // loads first.  The group of a chunk comes from one exact division per
-// workgroup step plus a small per-lane correction.
+// workgroup step plus a small per-lane correction.  THREADS is the size of the
+// workgroup the body runs in (the hosting kernel's).
 // ---------------------------------------------------------------------------
-template <int DT, int BITS, int UNROLL, bool HAS_BUF>
-__device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
+template <int DT, int BITS, int UNROLL, bool HAS_BUF, int THREADS>
+__device__ __forceinline__ void dequant_flat_body(const DequantJob& a, uint32_t bx, uint32_t by) {
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
-    constexpr uint32_t kStep = kBlock * UNROLL;
+    constexpr uint32_t kStep = THREADS * UNROLL;
     const uint32_t cpg = static_cast<uint32_t>(a.cpg);
     const float rcp_cpg = 1.0f / static_cast<float>(cpg);
     const uint32_t cps = static_cast<uint32_t>(a.cps);
-    for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
+    for (int i = by; i < a.batch; i += a.grid_y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
-        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         char* out_s = static_cast<char*>(a.out) + out0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
         const uint8_t* codes_s = a.codes + out0 / kChunk * BITS;
         const float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
-        for (uint32_t cbase = blockIdx.x * kStep; cbase < cps; cbase += gridDim.x * kStep) {
+        if constexpr (HAS_BUF) {
+            if (a.seen != nullptr) {
+                const bool fresh = __builtin_amdgcn_readfirstlane(first_visit(a.seen, row, a.stamp) ? 1 : 0) != 0;
+                if (fresh && bx == 0 && threadIdx.x == 0) a.seen[row] = a.stamp;       // one writer per sample
+                if (fresh) {             // first visit: the uncompressed row is the message
+                    const char* full_s = static_cast<const char*>(a.full) + out0 * kEB;
+                    for (uint32_t c = bx * THREADS + threadIdx.x; c < cps; c += a.grid_x * THREADS) {
+                        const Raw<DT> v = load_raw_at<DT>(full_s + static_cast<uint64_t>(c) * kChunkBytes);
+                        store_raw_at<DT>(m_s + static_cast<uint64_t>(c) * kChunkBytes, v);
+                        store_raw_at<DT>(out_s + static_cast<uint64_t>(c) * kChunkBytes, v);
+                    }
+                    continue;
+                }
+            }
+        }
+
+        for (uint32_t cbase = bx * kStep; cbase < cps; cbase += a.grid_x * kStep) {
             // group and position of the step's first chunk (uniform), then per lane
             const uint32_t g0 = cbase / cpg;
             const uint32_t r0 = cbase - g0 * cpg;
@@ -267,7 +361,7 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
             bool ok[UNROLL];
 #pragma unroll
             for (int u = 0; u < UNROLL; ++u) {
-                const uint32_t c = cbase + u * kBlock + threadIdx.x;       // chunk within the sample
+                const uint32_t c = cbase + u * THREADS + threadIdx.x;      // chunk within the sample
                 ok[u] = c < cps;
                 cs[u] = ok[u] ? c : cps - 1;
                 const uint32_t x = r0 + (cs[u] - cbase);                   // < cpg + kStep
@@ -314,23 +408,39 @@ __device__ __forceinline__ void dequant_flat_body(const DequantArgs& a) {
 // consecutive 16 bytes of m, out and, b/2 bytes each, of the codes.
 constexpr int64_t kMaxUnitChunks = int64_t{1} << 30;     // unit indices of a sample fit 32 bits
 
-template <int BITS, int UNITS, bool HAS_BUF>
-__device__ __forceinline__ void dequant_units_body(const DequantArgs& a) {
+template <int BITS, int UNITS, bool HAS_BUF, int THREADS>
+__device__ __forceinline__ void dequant_units_body(const DequantJob& a, uint32_t bx, uint32_t by) {
     constexpr int kUnitBytes = kUnit * 4;
-    constexpr uint32_t kStep = kBlock * UNITS;
+    constexpr uint32_t kStep = THREADS * UNITS;
     const uint32_t upg = 2u * static_cast<uint32_t>(a.cpg);              // units per group
     const float rcp_upg = 1.0f / static_cast<float>(upg);
     const uint32_t ups = 2u * static_cast<uint32_t>(a.cps);              // units per sample
-    for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
+    for (int i = by; i < a.batch; i += a.grid_y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
-        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         char* out_s = static_cast<char*>(a.out) + out0 * 4;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * 4 : nullptr;
         const uint8_t* codes_s = a.codes + out0 / kChunk * BITS;
         const float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
-        for (uint32_t ubase = blockIdx.x * kStep; ubase < ups; ubase += gridDim.x * kStep) {
+        if constexpr (HAS_BUF) {
+            if (a.seen != nullptr) {
+                const bool fresh = __builtin_amdgcn_readfirstlane(first_visit(a.seen, row, a.stamp) ? 1 : 0) != 0;
+                if (fresh && bx == 0 && threadIdx.x == 0) a.seen[row] = a.stamp;       // one writer per sample
+                if (fresh) {             // first visit: the uncompressed row is the message
+                    const char* full_s = static_cast<const char*>(a.full) + out0 * 4;
+                    for (uint32_t u = bx * THREADS + threadIdx.x; u < ups; u += a.grid_x * THREADS) {
+                        const f32x4_t v = __builtin_nontemporal_load(
+                            reinterpret_cast<const f32x4_t*>(full_s + static_cast<uint64_t>(u) * kUnitBytes));
+                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(m_s + static_cast<uint64_t>(u) * kUnitBytes));
+                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(out_s + static_cast<uint64_t>(u) * kUnitBytes));
+                    }
+                    continue;
+                }
+            }
+        }
+
+        for (uint32_t ubase = bx * kStep; ubase < ups; ubase += a.grid_x * kStep) {
             const uint32_t g0 = ubase / upg;
             const uint32_t r0 = ubase - g0 * upg;
             uint32_t w[UNITS];
@@ -340,7 +450,7 @@ __device__ __forceinline__ void dequant_units_body(const DequantArgs& a) {
             bool ok[UNITS];
 #pragma unroll
             for (int u = 0; u < UNITS; ++u) {
-                const uint32_t unit = ubase + u * kBlock + threadIdx.x;    // unit within the sample
+                const uint32_t unit = ubase + u * THREADS + threadIdx.x;   // unit within the sample
                 ok[u] = unit < ups;
                 us[u] = ok[u] ? unit : ups - 1;
                 const uint32_t x = r0 + (us[u] - ubase);                   // < upg + kStep
@@ -383,18 +493,75 @@ __device__ __forceinline__ void dequant_units_body(const DequantArgs& a) {
     }
 }
 
-template <int DT, int BITS, int UNROLL>
-__global__ __launch_bounds__(kBlock)
-void dequant_flat_kernel(const DequantArgs a) {
+// One dequantising job in a workgroup of THREADS lanes: the body for its bit width
+// and for with / without previous messages.
+template <int DT, int BITS, int UNROLL, int THREADS>
+__device__ __forceinline__ void dequant_job_bits(const DequantJob& a, uint32_t bx, uint32_t by) {
     if constexpr (UnitLayout<DT, BITS>::value) {
         if (a.cps <= kMaxUnitChunks) {                   // else the unit index would pass 32 bits
-            if (a.m_buf) dequant_units_body<BITS, 2 * UNROLL, true>(a);
-            else dequant_units_body<BITS, 2 * UNROLL, false>(a);
+            if (a.m_buf) dequant_units_body<BITS, 2 * UNROLL, true, THREADS>(a, bx, by);
+            else dequant_units_body<BITS, 2 * UNROLL, false, THREADS>(a, bx, by);
             return;
         }
     }
-    if (a.m_buf) dequant_flat_body<DT, BITS, UNROLL, true>(a);
-    else dequant_flat_body<DT, BITS, UNROLL, false>(a);
+    if (a.m_buf) dequant_flat_body<DT, BITS, UNROLL, true, THREADS>(a, bx, by);
+    else dequant_flat_body<DT, BITS, UNROLL, false, THREADS>(a, bx, by);
+}
+
+template <int DT, int UNROLL, int THREADS>
+__device__ __forceinline__ void dequant_job(const DequantJob& a, uint32_t bx, uint32_t by) {
+    switch (a.bits) {                                    // uniform over the workgroup
+    case 2: dequant_job_bits<DT, 2, UNROLL, THREADS>(a, bx, by); break;
+    case 3: dequant_job_bits<DT, 3, UNROLL, THREADS>(a, bx, by); break;
+    case 4: dequant_job_bits<DT, 4, UNROLL, THREADS>(a, bx, by); break;
+    case 6: dequant_job_bits<DT, 6, UNROLL, THREADS>(a, bx, by); break;
+    default: dequant_job_bits<DT, 8, UNROLL, THREADS>(a, bx, by); break;
+    }
+}
+
+// Workgroup number -> (job, position in the job's rectangle).  Jobs are listed in
+// ascending order of their first workgroup; everything here is uniform.
+template <typename Job>
+__device__ __forceinline__ int job_of_block(const Job* jobs, int n, uint32_t b) {
+    int j = 0;
+    for (int k = 1; k < n; ++k)
+        if (b >= jobs[k].block0) j = k;
+    return j;
+}
+
+constexpr int kHostedDequantUnroll = 2;      // dequantising jobs inside a quantising kernel's launch
+
+// The quantising jobs of one kernel configuration plus any dequantising jobs.
+template <int DT, int BITS, int ROUND, int TEAM, int CPL>
+__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
+void codec_jobs_kernel(const JobTable t) {
+    constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
+    static_assert(TEAM <= kWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
+    [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
+    const uint32_t b = blockIdx.x;
+    if (b < t.dequant_block0) {
+        const QuantJob& a = t.q[job_of_block(t.q, t.n_quant, b)];
+        const uint32_t local = b - a.block0;
+        const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
+        if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, bx, by, wave_max);
+        else quant_team_body<DT, BITS, ROUND, TEAM, CPL, false>(a, bx, by, wave_max);
+    } else {
+        const DequantJob& a = t.d[job_of_block(t.d, t.n_dequant, b)];
+        const uint32_t local = b - a.block0;
+        const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
+        dequant_job<DT, kHostedDequantUnroll, kThreads>(a, bx, by);
+    }
+}
+
+// Dequantising jobs alone.
+template <int DT, int UNROLL>
+__global__ __launch_bounds__(kBlock)
+void dequant_jobs_kernel(const JobTable t) {
+    const uint32_t b = blockIdx.x;
+    const DequantJob& a = t.d[job_of_block(t.d, t.n_dequant, b)];
+    const uint32_t local = b - a.block0;
+    const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
+    dequant_job<DT, UNROLL, kBlock>(a, bx, by);
 }
 
 // ---------------------------------------------------------------------------
@@ -404,18 +571,30 @@ void dequant_flat_kernel(const DequantArgs a) {
 // ---------------------------------------------------------------------------
 template <int DT>
 __global__ __launch_bounds__(kBlock)
-void quant_anyshape_kernel(const QuantArgs a, const int bits, const int rounding) {
+void quant_anyshape_kernel(const QuantJob a, const int bits, const int rounding) {
     const int L = (1 << bits) - 1;
     const float hL = static_cast<float>(L) / 2.0f;
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
-        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
+        bool fresh = false;
+        if (has_buf && a.seen != nullptr) {
+            fresh = first_visit(a.seen, row, a.stamp);
+            if (blockIdx.x == 0 && threadIdx.x == 0) {           // one writer per sample
+                a.first[i] = fresh ? 1 : 0;
+                if (fresh) a.seen[row] = a.stamp;
+            }
+        }
         for (int64_t gs = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; gs < a.gps;
              gs += static_cast<int64_t>(gridDim.x) * kBlock) {
             const int64_t goff = gs * a.group;
+            if (fresh) {                                         // first visit: the row itself is the message
+                for (int e = 0; e < a.group; ++e)
+                    store_elem<DT>(a.m_buf, m0 + goff + e, load_elem<DT>(a.src, src0 + goff + e));
+                continue;
+            }
             float mx = 0.0f;
             for (int e = 0; e < a.group; ++e) {
                 const float m_old = has_buf ? load_elem<DT>(a.m_buf, m0 + goff + e) : 0.0f;
@@ -464,18 +643,31 @@ void quant_anyshape_kernel(const QuantArgs a, const int bits, const int rounding
 
 template <int DT>
 __global__ __launch_bounds__(kBlock)
-void dequant_anyshape_kernel(const DequantArgs a, const int bits) {
+void dequant_anyshape_kernel(const DequantJob a) {
+    const int bits = a.bits;
     const int L = (1 << bits) - 1;
     const float hL = static_cast<float>(L) / 2.0f;
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
         const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
-        if (a.seen != nullptr && a.seen[row] == 0) continue;     // first visit: handled by the row copy
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
+        bool fresh = false;
+        if (has_buf && a.seen != nullptr) {
+            fresh = first_visit(a.seen, row, a.stamp);
+            if (fresh && blockIdx.x == 0 && threadIdx.x == 0) a.seen[row] = a.stamp;   // one writer per sample
+        }
         for (int64_t gs = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; gs < a.gps;
              gs += static_cast<int64_t>(gridDim.x) * kBlock) {
             const int64_t goff = gs * a.group;
+            if (fresh) {                                         // first visit: the uncompressed row arrives
+                for (int e = 0; e < a.group; ++e) {
+                    const float v = load_elem<DT>(a.full, out0 + goff + e);
+                    store_elem<DT>(a.m_buf, m0 + goff + e, v);
+                    store_elem<DT>(a.out, out0 + goff + e, v);
+                }
+                continue;
+            }
             const float scale = a.scales[static_cast<int64_t>(i) * a.gps + gs];
             const bool live = scale != 0.0f;
             const float step = (live ? scale : 1.0f) / hL;
@@ -505,7 +697,8 @@ void dequant_anyshape_kernel(const DequantArgs a, const int bits) {
 // ---------------------------------------------------------------------------
 // Launch tables, one set per dtype translation unit.
 // ---------------------------------------------------------------------------
-struct LaunchGeom { unsigned grid_x, grid_y; };
+
+struct LaunchGeom { uint32_t grid_x, grid_y; };
 
 // Optional timing of the next launch made by this host thread: when set (see
 // aqsgd_profile_next_launch) the kernel goes out through hipExtLaunchKernel,
@@ -514,22 +707,23 @@ struct LaunchGeom { unsigned grid_x, grid_y; };
 struct ProfileRequest { hipEvent_t start, stop; };
 extern thread_local ProfileRequest g_profile_request;
 
+// Returns the status of this launch alone (an earlier error that the calling
+// thread has not collected is neither reported here nor cleared).
 template <typename... KArgs, typename... Args>
 hipError_t launch_kernel(void (*kernel)(KArgs...), dim3 grid, dim3 block, hipStream_t stream,
                          Args... args) {
+    std::tuple<KArgs...> held(args...);
+    void* argv[sizeof...(KArgs)];
+    fill_arg_pointers(held, argv, std::index_sequence_for<KArgs...>{});
     ProfileRequest& pr = g_profile_request;
     if (pr.start || pr.stop) {
-        std::tuple<KArgs...> held(args...);
-        void* argv[sizeof...(KArgs)];
-        fill_arg_pointers(held, argv, std::index_sequence_for<KArgs...>{});
         const hipError_t err = hipExtLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv,
                                                   0, stream, pr.start, pr.stop, 0);
         pr.start = nullptr;
         pr.stop = nullptr;
         return err;
     }
-    hipLaunchKernelGGL(kernel, grid, block, 0, stream, args...);
-    return hipGetLastError();
+    return hipLaunchKernel(reinterpret_cast<const void*>(kernel), grid, block, argv, 0, stream);
 }
 
 // Team shapes the dispatcher may pick; index into the table below.
@@ -538,23 +732,20 @@ enum TeamShape {
     kTeam256x2, kTeam256x4, kTeam1024x2, kTeam1024x4, kNumTeamShapes
 };
 
-hipError_t launch_quant_team(int dtype, int bits, int rounding, int shape, LaunchGeom g,
-                             const QuantArgs& a, hipStream_t stream);
-hipError_t launch_dequant_flat(int dtype, int bits, int unroll, LaunchGeom g, const DequantArgs& a,
-                               hipStream_t stream);
-hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, LaunchGeom g, const QuantArgs& a,
-                                 hipStream_t stream);
-hipError_t launch_dequant_anyshape(int dtype, int bits, LaunchGeom g, const DequantArgs& a,
-                                   hipStream_t stream);
+// A launch of codec_jobs_kernel (the table's quantising jobs all have this bit width,
+// rounding mode and team shape) or, with no quantising job, of dequant_jobs_kernel.
+hipError_t launch_codec_jobs(int dtype, int bits, int rounding, int shape, const JobTable& t,
+                             hipStream_t stream);
+hipError_t launch_dequant_jobs(int dtype, int unroll, const JobTable& t, hipStream_t stream);
+hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, const QuantJob& a, hipStream_t stream);
+hipError_t launch_dequant_anyshape(int dtype, const DequantJob& a, hipStream_t stream);
 
 // Per-dtype pieces (defined by AQSGD_INSTANTIATE_DTYPE in the dtype's .hip file).
-template <int DT> hipError_t launch_quant_team_dt(int bits, int rounding, int shape, LaunchGeom g,
-                                                  const QuantArgs& a, hipStream_t stream);
-template <int DT> hipError_t launch_dequant_flat_dt(int bits, int unroll, LaunchGeom g,
-                                                    const DequantArgs& a, hipStream_t stream);
-template <int DT> hipError_t launch_quant_anyshape_dt(int bits, int rounding, LaunchGeom g,
-                                                      const QuantArgs& a, hipStream_t stream);
-template <int DT> hipError_t launch_dequant_anyshape_dt(int bits, LaunchGeom g, const DequantArgs& a,
-                                                        hipStream_t stream);
+template <int DT> hipError_t launch_codec_jobs_dt(int bits, int rounding, int shape, const JobTable& t,
+                                                  hipStream_t stream);
+template <int DT> hipError_t launch_dequant_jobs_dt(int unroll, const JobTable& t, hipStream_t stream);
+template <int DT> hipError_t launch_quant_anyshape_dt(int bits, int rounding, const QuantJob& a,
+                                                      hipStream_t stream);
+template <int DT> hipError_t launch_dequant_anyshape_dt(const DequantJob& a, hipStream_t stream);
 
 }  // namespace aqsgd

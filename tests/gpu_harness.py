@@ -10,6 +10,7 @@ import numpy as np
 import torch
 
 import oracle
+from oracle.boundary import OracleBoundary
 from paper_2206_01299_amd import binding as B
 from paper_2206_01299_amd import workloads as W
 
@@ -89,36 +90,6 @@ class DeviceBoundary:
 class _null:
     def __enter__(self): return self
     def __exit__(self, *a): return False
-
-
-class OracleBoundary:
-    """The same boundary on the host, holding only the visited rows of m."""
-
-    def __init__(self, cfg: W.BoundaryConfig, visited: np.ndarray):
-        self.cfg = cfg
-        self.order = np.sort(np.asarray(visited, dtype=np.int64))
-        self.local = {int(s): i for i, s in enumerate(self.order)}
-        npdt = W.storage_numpy_dtype(cfg.dtype)
-        self.m_send = np.zeros((len(self.order), cfg.n_per), dtype=npdt)
-        self.m_recv = np.zeros((len(self.order), cfg.n_per), dtype=npdt)
-
-    def forward(self, act_np: np.ndarray, ids_np: np.ndarray, seed: int):
-        c = self.cfg
-        loc = np.array([self.local[int(s)] for s in ids_np], dtype=np.int64)
-        act = np.ascontiguousarray(act_np.reshape(c.batch, c.n_per))
-        codes, scales = oracle.encode(act, loc, self.m_send, dtype=c.dtype, bits=c.fwd_bits,
-                                      group=c.fwd_group, rounding=c.fwd_rounding, seed=seed)
-        out = oracle.decode(codes, scales, loc, self.m_recv, dtype=c.dtype, bits=c.fwd_bits,
-                            group=c.fwd_group)
-        return codes, scales, out
-
-    def backward(self, grad_np: np.ndarray, seed: int):
-        c = self.cfg
-        g = np.ascontiguousarray(grad_np.reshape(-1))
-        codes, scales = oracle.grad_quant(g, dtype=c.dtype, bits=c.bwd_bits, group=c.bwd_group,
-                                          rounding=c.bwd_rounding, seed=seed)
-        out = oracle.grad_dequant(codes, scales, dtype=c.dtype, bits=c.bwd_bits, group=c.bwd_group)
-        return codes, scales, out
 
 
 def compare_call(tag: str, cfg, got, want) -> None:

@@ -1,7 +1,8 @@
 """GPU parity of Algorithm 1 with its first-visit branch (aqsgd_encode_seen /
 aqsgd_decode_seen) against the CPU oracle: a stream in which new samples keep
 appearing, so calls mix first visits (uncompressed, seed m) with later visits
-(quantised change).  Every byte the calls define is compared."""
+(quantised change).  Every byte the calls define is compared; the library's 32-bit
+first-visit stamps are compared with the oracle's flags as zero / non-zero."""
 import numpy as np
 import pytest
 import torch
@@ -30,7 +31,7 @@ def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed):
     rng = np.random.default_rng(seed)
     base = rng.standard_normal((n_rows, n_per)).astype(np.float32)
     m_s = torch.zeros((n_rows, n_per), dtype=td, device=d); m_r = torch.zeros_like(m_s)
-    seen_s = torch.zeros(n_rows, dtype=torch.uint8, device=d); seen_r = torch.zeros_like(seen_s)
+    seen_s = torch.zeros(n_rows, dtype=torch.int32, device=d); seen_r = torch.zeros_like(seen_s)
     npdt = W.to_storage(np.zeros(1, dtype=np.float32), dtype).dtype
     om_s = np.zeros((n_rows, n_per), dtype=npdt); om_r = om_s.copy()
     oseen_s = np.zeros(n_rows, dtype=np.uint8); oseen_r = oseen_s.copy()
@@ -48,10 +49,10 @@ def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed):
         scales = torch.full((B.scales_count(desc),), float(0x5A), dtype=torch.float32, device=d)
         first = torch.full((batch,), -7, dtype=torch.int32, device=d)
         out = W.to_torch(W.to_storage(np.full((batch, n_per), 9.0, dtype=np.float32), dtype), dtype, d)
-        B.encode_seen(desc, act, ids, m_s, seen_s, first, codes, scales)
+        B.encode_seen(desc, act, ids, m_s, seen_s, 1 + step, first, codes, scales)
         # the receiver is handed the uncompressed rows of the first visits only
         full = torch.where(first.view(-1, 1) == 1, act.view(batch, n_per), torch.zeros_like(act.view(batch, n_per)))
-        B.decode_seen(desc, codes, scales, full.contiguous(), ids, m_r, seen_r, out)
+        B.decode_seen(desc, codes, scales, full.contiguous(), ids, m_r, seen_r, 77 + step, out)
         torch.cuda.synchronize()
 
         wf, wc, ws = oracle.encode_seen(a_np, ids_np, om_s, oseen_s, dtype=dtype, bits=bits, group=group,
@@ -66,7 +67,8 @@ def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed):
         assert H.same_bytes(got, wo), f"{tag}: out: {H.first_diff(got, wo)}"
         assert H.same_bytes(W.from_torch(m_s, dtype), om_s), f"{tag}: sender m"
         assert H.same_bytes(W.from_torch(m_r, dtype), om_r), f"{tag}: receiver m"
-        assert np.array_equal(seen_s.cpu().numpy(), oseen_s) and np.array_equal(seen_r.cpu().numpy(), oseen_r)
+        assert np.array_equal(seen_s.cpu().numpy() != 0, oseen_s != 0), f"{tag}: sender's seen words"
+        assert np.array_equal(seen_r.cpu().numpy() != 0, oseen_r != 0), f"{tag}: receiver's seen words"
         firsts += int(wf.sum())
     assert 0 < firsts < steps * batch            # the stream really mixed first and later visits
 
@@ -92,8 +94,10 @@ def test_seen_entry_points_reject_bad_arguments(H):
     L = B.lib()
     p = ctypes.c_void_p(4096)
     ok = B.make_desc(batch=2, n_per=1600, n_samples=4, bits=4, group=1600, dtype="f16")
-    assert L.aqsgd_encode_seen(ctypes.byref(ok), p, p, p, None, p, p, p, None) == -1
-    assert L.aqsgd_decode_seen(ctypes.byref(ok), p, p, None, p, p, p, p, None) == -1
-    assert L.aqsgd_encode_seen(ctypes.byref(ok), p, p, p, p, ctypes.c_void_p(4098), p, p, None) == -6
+    assert L.aqsgd_encode_seen(ctypes.byref(ok), p, p, p, None, 1, p, p, p, None) == -1
+    assert L.aqsgd_decode_seen(ctypes.byref(ok), p, p, None, p, p, p, 1, p, None) == -1
+    assert L.aqsgd_encode_seen(ctypes.byref(ok), p, p, p, p, 1, ctypes.c_void_p(4098), p, p, None) == -6
+    assert L.aqsgd_encode_seen(ctypes.byref(ok), p, p, p, p, 0, p, p, p, None) == -5        # stamp 0
+    assert L.aqsgd_decode_seen(ctypes.byref(ok), p, p, p, p, p, p, 0, p, None) == -5
     bad = B.make_desc(batch=2, n_per=1600, n_samples=4, bits=5, group=1600, dtype="f16")
-    assert L.aqsgd_encode_seen(ctypes.byref(bad), p, p, p, p, p, p, p, None) == -2
+    assert L.aqsgd_encode_seen(ctypes.byref(bad), p, p, p, p, 1, p, p, p, None) == -2

@@ -2,8 +2,8 @@
 
   * m starts at 0 (Algorithm 1, initialisation), so a first visit is direct
     quantisation of the activation.
-  * Sender and receiver apply the same update, so their copies of m stay
-    identical (Section 3.1, "Both machines then update this local buffer").
+  * Sender and receiver apply the same update to their own copy of m, so the
+    two copies stay identical (Section 3.1).
   * The activation handed to the next stage is m(xi) (Algorithm 2, network b).
   * |a - m_new| is bounded by the group's level half-spacing (Theorem 3.1's
     requirement on Q, elementwise), plus the storage rounding.
