@@ -76,11 +76,15 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--streams", type=int, choices=[1, 2, 4, 8], default=4,
+    ap.add_argument("--streams", type=int, choices=[1, 2, 4, 8], default=2,
                     help="1: the four kernels of a step run one after the other on one stream; "
                          "N>1: N/2 streams carry forward pairs (encode then decode of one micro-batch) "
                          "and N/2 carry backward pairs, micro-batches dealt round-robin; micro-batches "
                          "touch disjoint samples and pool slots, so the chains are independent")
+    ap.add_argument("--schedule", choices=["calls", "stage", "pipeline"], default="pipeline",
+                    help="calls: four single-message calls per step; stage / pipeline: the same messages "
+                         "through aqsgd_run_jobs, two launches (one per stage) or one launch (one time "
+                         "slot of both stages) per micro-batch")
     ap.add_argument("--pool", type=int, default=0,
                     help="micro-batch slots per rotating pool (0 = enough for 1.25 GB per pool)")
     ap.add_argument("--config", default="gpt2_4bit",
@@ -237,6 +241,54 @@ class Workload:
         else:
             self.B.grad_dequant(self.bdesc, self.bcodes[s], self.bscales[s], self.gout[s])
 
+    # -- the same four messages as jobs of one aqsgd_run_jobs call ------------------
+    def job(self, leg, k):
+        s, B = k % self.pool, self.B
+        if leg == "encode":
+            self.fdesc.rng_seed = 0x5EED0000 + 2 * k
+            return B.encode_job(self.fdesc, self.act[s], self.ids[k % self.calls], self.m_send,
+                                self.codes[s], self.scales[s])
+        if leg == "decode":
+            return B.decode_job(self.fdesc, self.codes[s], self.scales[s], self.ids[k % self.calls],
+                                self.m_recv, self.out[s])
+        if leg == "grad_quant":
+            self.bdesc.rng_seed = 0x5EED0001 + 2 * k
+            return B.grad_quant_job(self.bdesc, self.grad[s], self.bcodes[s], self.bscales[s])
+        return B.grad_dequant_job(self.bdesc, self.bcodes[s], self.bscales[s], self.gout[s])
+
+    def fused_chain(self, ks, schedule, backward=True):
+        """The messages of micro-batches `ks` (in this order) on the current stream, in
+        launches that carry several independent jobs.
+        stage:    what each stage of the boundary launches: the sending stage encode(k) together
+                  with grad_dequant of the micro-batch before, the receiving stage decode(k)
+                  together with grad_quant(k); two launches per micro-batch.
+        pipeline: both stages' work of one time slot in one launch, as when the two stages
+                  work on neighbouring micro-batches at the same time: encode(k), decode and
+                  grad_quant of the micro-batch before, grad_dequant of the one before that.
+        Every message of every micro-batch in `ks` is launched exactly once."""
+        B, n = self.B, len(ks)
+        if schedule == "stage":
+            for t in range(n):
+                B.run_jobs([self.job("encode", ks[t])] +
+                           ([self.job("grad_dequant", ks[t - 1])] if backward and t >= 1 else []))
+                B.run_jobs([self.job("decode", ks[t])] + ([self.job("grad_quant", ks[t])] if backward else []))
+            if backward and n:
+                B.run_jobs([self.job("grad_dequant", ks[-1])])
+            return
+        assert schedule == "pipeline"
+        for t in range(n + (2 if backward else 1)):
+            jobs = []
+            if t < n:
+                jobs.append(self.job("encode", ks[t]))
+            if 0 <= t - 1 < n:
+                jobs.append(self.job("decode", ks[t - 1]))
+                if backward:
+                    jobs.append(self.job("grad_quant", ks[t - 1]))
+            if backward and 0 <= t - 2 < n:
+                jobs.append(self.job("grad_dequant", ks[t - 2]))
+            if jobs:
+                B.run_jobs(jobs)
+
     LEGS = ("encode", "decode", "grad_quant", "grad_dequant")
 
     def step(self, k, backward=True):
@@ -335,7 +387,36 @@ def evict_caches(torch, scratch):
     torch.cuda.synchronize()
 
 
-def timed_steps(wl, first, count, launch, n_streams, backward=True):
+def enqueue_steps(wl, main, k0, k1, n_streams, schedule, backward=True):
+    """Steps k0..k1-1 onto `main` (one stream), or fanned out from / joined back into it
+    (wl.make_streams(n_streams) made the streams; micro-batches are dealt round-robin)."""
+    torch = wl.torch
+    if n_streams == 1:
+        with torch.cuda.stream(main):
+            if schedule == "calls":
+                for k in range(k0, k1):
+                    wl.step(k, backward)
+            else:
+                wl.fused_chain(list(range(k0, k1)), schedule, backward)
+        return
+    fork = torch.cuda.Event()
+    fork.record(main)
+    for st in wl.streams:
+        st.wait_event(fork)
+    if schedule == "calls":
+        for k in range(k0, k1):
+            wl.step_on_streams(k, backward)
+    else:
+        for i, st in enumerate(wl.streams):
+            with torch.cuda.stream(st):
+                wl.fused_chain(list(range(k0 + i, k1, n_streams)), schedule, backward)
+    for st in wl.streams:
+        done = torch.cuda.Event()
+        done.record(st)
+        main.wait_event(done)
+
+
+def timed_steps(wl, first, count, launch, n_streams, backward=True, schedule="calls"):
     """Run `count` steps starting at step index `first`; returns (device seconds, wall
     seconds) of the whole region.  In graph mode the graphs are built, instantiated and
     replayed once before the clock starts (the first replay of a new graph uploads it);
@@ -347,21 +428,7 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True):
     clock = DeviceClock(torch, main)
 
     def enqueue(k0, k1):
-        """Steps k0..k1-1 onto `main` (one stream) or fanned out from / joined back into it."""
-        if n_streams == 1:
-            for k in range(k0, k1):
-                wl.step(k, backward)
-            return
-        fork = torch.cuda.Event()
-        fork.record(main)
-        for st in wl.streams:
-            st.wait_event(fork)
-        for k in range(k0, k1):
-            wl.step_on_streams(k, backward)
-        for st in wl.streams:
-            done = torch.cuda.Event()
-            done.record(st)
-            main.wait_event(done)
+        enqueue_steps(wl, main, k0, k1, n_streams, schedule, backward)
 
     if launch == "eager":
         # the spin must outlast the host's enqueueing of every launch (about 10 us each)
@@ -437,13 +504,24 @@ def stream_copy_ceiling(torch, nbytes=1 << 30, reps=5):
     return 2.0 * nbytes * reps / (a.elapsed_time(b) * 1e-3) / 1e9
 
 
-def kernel_legs(wl, first, count):
-    """Per-launch device durations of every leg over `count` steps (HIP events
-    stamped by the launch itself, on the stream the kernel runs on)."""
+def kernel_legs(wl, first, count, schedule="calls"):
+    """Per-launch device durations over `count` steps (HIP events stamped by the launch
+    itself, on the stream the kernel runs on), every launch on its own, one after the
+    other: the four single-message calls, and the launches of the fused schedule (a
+    launch that carries several jobs is timed as the one kernel it is)."""
     torch, B = wl.torch, wl.B
     count = min(count, 1024)
-    pairs = {leg: [] for leg in wl.LEGS}
-    for leg in wl.LEGS:
+    fused = {}
+    one_launch = (wl.cfg.fwd_rounding == wl.cfg.bwd_rounding and wl.cfg.fwd_group == wl.cfg.bwd_group
+                  and (wl.cfg.fwd_bits == 3) == (wl.cfg.bwd_bits == 3) and not wl.m_bits and not wl.keep)
+    if schedule == "stage" and not wl.m_bits and not wl.keep:
+        fused = {"sender_launch(encode+grad_dequant)": ("encode", "grad_dequant"),
+                 "receiver_launch(decode+grad_quant)": ("decode", "grad_quant")}
+    elif schedule == "pipeline" and one_launch:
+        fused = {"slot_launch(encode+decode+grad_quant+grad_dequant)": wl.LEGS}
+    names = list(wl.LEGS) + list(fused)
+    pairs = {leg: [] for leg in names}
+    for leg in names:
         for _ in range(count):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(); b.record()                       # creates the HIP events
@@ -455,12 +533,21 @@ def kernel_legs(wl, first, count):
             B.profile_next_launch(a, b)
             getattr(wl, leg)(k)
     torch.cuda.synchronize()
+    # fused launches: the jobs of one launch come from different micro-batches, as in the
+    # schedule (encode k, decode / grad_quant k-1, grad_dequant k-2), so they are independent
+    lag = {"encode": 0, "decode": 1, "grad_quant": 1, "grad_dequant": 2}
+    for name, members in fused.items():
+        for i, k in enumerate(range(first + count, first + 2 * count)):
+            a, b = pairs[name][i]
+            B.profile_next_launch(a, b)
+            B.run_jobs([wl.job(m, k - lag[m]) for m in members])
+    torch.cuda.synchronize()
     out = {}
-    for leg in wl.LEGS:
+    for leg in names:
         ms = [a.elapsed_time(b) for a, b in pairs[leg]]
         ms.sort()
         out[leg] = {"avg_us": 1e3 * sum(ms) / len(ms), "median_us": 1e3 * ms[len(ms) // 2],
-                    "min_us": 1e3 * ms[0], "launches": len(ms)}
+                    "min_us": 1e3 * ms[0], "launches": len(ms), "members": fused.get(leg, (leg,))}
     return out
 
 
@@ -574,18 +661,25 @@ def main():
     torch.cuda.synchronize()
 
     # K whole steps, then the forward messages of the same K micro-batches alone
-    step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams)
-    fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False)
+    sched = args.schedule
+    if args.m_bits or args.bwd_keep:
+        sched = "calls"                                  # these variants have single-message calls only
+    step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams, schedule=sched)
+    fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False, schedule=sched)
     ms_per_step = step_dev / K * 1e3
     act_bytes = cfg.n * cfg.elem_bytes
     value = act_bytes / (fwd_dev / K) / 1e9              # the metric: encode + decode, activation bytes
 
-    legs = None if args.no_kernel_legs else kernel_legs(wl, Wm, K)
+    legs = None if args.no_kernel_legs else kernel_legs(wl, Wm, max(K, 64), sched)
     lb = wl.leg_bytes()
     roofline = None
     extra = {}
     if legs:
-        dominant = max(wl.LEGS, key=lambda l: legs[l]["avg_us"])
+        for l in legs:                                   # a fused launch moves its members' bytes
+            lb.setdefault(l, sum(lb[m] for m in legs[l]["members"]))
+        # the dominant kernel: the longest launch among those the timed schedule makes
+        in_schedule = [l for l in legs if l not in wl.LEGS] or list(wl.LEGS)
+        dominant = max(in_schedule, key=lambda l: legs[l]["avg_us"])
         a_gbps = lb[dominant] / (legs[dominant]["avg_us"] * 1e-6) / 1e9
         traffic = (read_traffic() if args.config == "gpt2_4bit" and not args.m_bits and not args.bwd_keep
                    else None)
@@ -593,6 +687,7 @@ def main():
                     "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": round(a_gbps / HBM_PEAK_GBPS, 4),
                     "algorithmic_bytes_per_launch": lb[dominant],
                     "avg_launch_us": round(legs[dominant]["avg_us"], 3),
+                    "launches_timed": legs[dominant]["launches"],
                     "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch"),
                     "traffic_source": "stored rocprofv3 counter value (profiles/hbm_traffic_gpt2_fw4.txt), "
                                       "not measured in this run" if traffic else None}
@@ -604,9 +699,9 @@ def main():
                              "frac_of_hbm_peak": round(pair_bytes / pair_us / 1e3 / HBM_PEAK_GBPS, 4)}
         extra["kernels"] = {l: {"avg_us": round(legs[l]["avg_us"], 3),
                                 "median_us": round(legs[l]["median_us"], 3),
-                                "hbm_GBps": round(lb[l] / legs[l]["avg_us"] / 1e3, 1)} for l in wl.LEGS}
+                                "hbm_GBps": round(lb[l] / legs[l]["avg_us"] / 1e3, 1)} for l in legs}
     fwd_bytes = lb["encode"] + lb["decode"]
-    step_bytes = sum(lb.values())
+    step_bytes = sum(lb[l] for l in wl.LEGS)
     extra["fwd_only"] = {"us_per_microbatch": round(fwd_dev / K * 1e6, 3),
                          "act_GBps": round(value, 1),
                          "hbm_GBps": round(fwd_bytes / (fwd_dev / K) / 1e9, 1),
@@ -655,7 +750,7 @@ def main():
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
                    "group": cfg.fwd_group, "m_bits": args.m_bits or None, "bwd_keep": args.bwd_keep or None,
-                   "pool_slots": args.pool, "launch": args.launch,
+                   "pool_slots": args.pool, "launch": args.launch, "schedule": sched,
                    "streams": args.streams,
                    "cold_buffers": True, "device": torch.cuda.get_device_name(0),
                    "setup_s": round(t_setup, 1)},

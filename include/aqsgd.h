@@ -153,7 +153,7 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
  * reads what another writes, and no two touch the same row of the same m_buf; they run
  * concurrently, in no particular order.  Results are bit-identical to the single calls.
  * How jobs share launches: quantising jobs (ENCODE, GRAD_QUANT) with the same dtype,
- * bits, rounding and group-size class share one grid, and the dequantising jobs of that
+ * rounding and group-size class (and either all 3-bit or none 3-bit) share one grid, and the dequantising jobs of that
  * dtype join it; dequantising jobs without such a host share a grid of their own; up to
  * 8 + 8 jobs per grid, more are split; jobs whose group is not a multiple of 8 or larger
  * than 32768 run on their own.  The typical stage-side call (one ENCODE and one

@@ -12,8 +12,11 @@ from pathlib import Path
 
 import torch
 
+import os
+
 _HERE = Path(__file__).resolve().parent
-LIB_PATH = _HERE / "libaqsgd.so"
+# AQSGD_LIB names another build of the same library (used to compare two builds in one session)
+LIB_PATH = Path(os.environ["AQSGD_LIB"]) if os.environ.get("AQSGD_LIB") else _HERE / "libaqsgd.so"
 
 F32, F16, BF16 = 0, 1, 2
 NEAREST, STOCHASTIC = 0, 1

@@ -14,11 +14,11 @@ namespace aqsgd {
 thread_local ProfileRequest g_profile_request = {nullptr, nullptr};
 
 // -- dtype fan-out (each dtype's kernels live in their own translation unit) ----
-hipError_t launch_codec_jobs(int dtype, int bits, int rounding, int shape, const JobTable& t, hipStream_t s) {
+hipError_t launch_codec_jobs(int dtype, int rounding, int shape, bool three, const JobTable& t, hipStream_t s) {
     switch (dtype) {
-    case AQSGD_F32:  return launch_codec_jobs_dt<AQSGD_F32>(bits, rounding, shape, t, s);
-    case AQSGD_F16:  return launch_codec_jobs_dt<AQSGD_F16>(bits, rounding, shape, t, s);
-    case AQSGD_BF16: return launch_codec_jobs_dt<AQSGD_BF16>(bits, rounding, shape, t, s);
+    case AQSGD_F32:  return launch_codec_jobs_dt<AQSGD_F32>(rounding, shape, three, t, s);
+    case AQSGD_F16:  return launch_codec_jobs_dt<AQSGD_F16>(rounding, shape, three, t, s);
+    case AQSGD_BF16: return launch_codec_jobs_dt<AQSGD_BF16>(rounding, shape, three, t, s);
     default:         return hipErrorInvalidValue;
     }
 }
@@ -176,8 +176,8 @@ QuantPlan plan_quant(const aqsgd_desc* d, int64_t batch, int64_t n_per, const vo
     QuantJob& a = p.job;
     a.src = src; a.ids = ids; a.m_buf = m_buf; a.codes = codes; a.scales = scales;
     a.n_per = n_per; a.gps = n_per / d->group;
-    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk;
-    a.block0 = 0; a.grid_x = a.grid_y = 1;
+    a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk; a.bits = d->bits;
+    a.grid_x = a.grid_y = 1; a.rcp_grid_x = 1.0f;
     a.seed = d->rng_seed; a.seen = sa.seen; a.first = sa.first; a.stamp = sa.stamp;
     p.dtype = d->dtype; p.bits = d->bits; p.rounding = d->rounding;
     p.shape = (d->group % kChunk == 0 && a.cpg <= kMaxTeamChunks) ? team_shape_for(a.cpg) : -1;
@@ -199,19 +199,21 @@ DequantPlan plan_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, cons
     a.codes = codes; a.scales = scales; a.ids = ids; a.m_buf = m_buf; a.out = out; a.full = sa.full;
     a.n_per = n_per; a.gps = n_per / d->group; a.cps = n_per / kChunk;
     a.batch = static_cast<int32_t>(batch); a.group = d->group; a.cpg = d->group / kChunk; a.bits = d->bits;
-    a.block0 = 0; a.grid_x = a.grid_y = 1;
+    a.grid_x = a.grid_y = 1; a.rcp_grid_x = 1.0f;
     a.seen = sa.seen; a.stamp = sa.stamp;
     p.dtype = d->dtype;
     p.flat = d->group % kChunk == 0;
     return p;
 }
 
-// The launches of a set of independent messages: quantising jobs that share dtype, bit
-// width, rounding mode and team shape go into one grid, together with the dequantising
+// The launches of a set of independent messages: quantising jobs that share dtype,
+// rounding mode, team shape and bit-width class (3 bits or not) go into one grid, together with the dequantising
 // jobs of that dtype that are still waiting; dequantising jobs without such a host get a
 // grid of their own; jobs that need the any-shape kernels are launched one by one.
 int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipStream_t stream) {
-    const int64_t max_blocks = max_blocks_knob().load(std::memory_order_relaxed);
+    // a job's workgroup numbers must be exact in binary32 (place_in_job)
+    const int64_t knob = max_blocks_knob().load(std::memory_order_relaxed);
+    const int64_t max_blocks = knob < (int64_t{1} << 24) ? knob : (int64_t{1} << 24) - 1;
     const int unroll = dequant_unroll_knob().load(std::memory_order_relaxed);
     std::vector<bool> q_done(qs.size(), false), d_done(ds.size(), false);
     hipError_t err = hipSuccess;
@@ -221,7 +223,8 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
             if (d_done[k] || !ds[k].flat || ds[k].dtype != dtype) continue;
             DequantJob a = ds[k].job;
             const LaunchGeom g = geometry(a.cps, static_cast<int64_t>(threads) * job_unroll, a.batch, max_blocks);
-            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.block0 = static_cast<uint32_t>(blocks);
+            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
+            t.d_block0[t.n_dequant] = static_cast<uint32_t>(blocks);
             blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
             t.d[t.n_dequant++] = a;
             d_done[k] = true;
@@ -243,12 +246,13 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         int64_t blocks = 0;
         for (size_t k = i; k < qs.size() && t.n_quant < kMaxQuantJobs; ++k) {
             const QuantPlan& c = qs[k];
-            if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.bits != lead.bits ||
-                c.rounding != lead.rounding)
+            if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.rounding != lead.rounding ||
+                (c.bits == 3) != (lead.bits == 3))
                 continue;
             QuantJob a = c.job;
             const LaunchGeom g = geometry(a.gps, teams_per_block(c.shape), a.batch, max_blocks);
-            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.block0 = static_cast<uint32_t>(blocks);
+            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
+            t.q_block0[t.n_quant] = static_cast<uint32_t>(blocks);
             blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
             t.q[t.n_quant++] = a;
             q_done[k] = true;
@@ -256,7 +260,7 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         t.dequant_block0 = static_cast<uint32_t>(blocks);
         add_dequant(t, lead.dtype, threads_of_shape(lead.shape), kHostedDequantUnroll, blocks);
         t.total_blocks = static_cast<uint32_t>(blocks);
-        err = launch_codec_jobs(lead.dtype, lead.bits, lead.rounding, lead.shape, t, stream);
+        err = launch_codec_jobs(lead.dtype, lead.rounding, lead.shape, lead.bits == 3, t, stream);
     }
     for (size_t i = 0; i < ds.size() && err == hipSuccess; ++i) {
         if (d_done[i]) continue;

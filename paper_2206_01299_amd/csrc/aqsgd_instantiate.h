@@ -1,5 +1,5 @@
-// Launch tables of one storage dtype: every (bits, rounding, team shape) of the
-// job kernel that hosts quantising jobs and every unroll of the one that holds
+// Launch tables of one storage dtype: every (rounding, team shape, 3-bit or not) of the job
+// kernel that hosts quantising jobs and every unroll of the one that holds
 // dequantising jobs alone.  Each dtype gets its own translation unit so the three
 // compile in parallel.
 #pragma once
@@ -8,48 +8,38 @@
 
 namespace aqsgd {
 
-template <int DT, int BITS, int ROUND, int TEAM, int CPL>
+template <int DT, int ROUND, bool THREE, int TEAM, int CPL>
 static hipError_t launch_cj(const JobTable& t, hipStream_t stream) {
     constexpr int threads = TEAM > kWave ? TEAM : kBlock;
-    return launch_kernel(codec_jobs_kernel<DT, BITS, ROUND, TEAM, CPL>, dim3(t.total_blocks), dim3(threads),
+    return launch_kernel(codec_jobs_kernel<DT, ROUND, TEAM, CPL, THREE>, dim3(t.total_blocks), dim3(threads),
                          stream, t);
 }
 
-template <int DT, int BITS, int ROUND>
+template <int DT, int ROUND, bool THREE>
 static hipError_t launch_cj_shape(int shape, const JobTable& t, hipStream_t stream) {
     switch (shape) {
-    case kTeam8x1:    return launch_cj<DT, BITS, ROUND, 8, 1>(t, stream);
-    case kTeam16x1:   return launch_cj<DT, BITS, ROUND, 16, 1>(t, stream);
-    case kTeam32x1:   return launch_cj<DT, BITS, ROUND, 32, 1>(t, stream);
-    case kTeam64x1:   return launch_cj<DT, BITS, ROUND, 64, 1>(t, stream);
-    case kTeam64x2:   return launch_cj<DT, BITS, ROUND, 64, 2>(t, stream);
-    case kTeam64x3:   return launch_cj<DT, BITS, ROUND, 64, 3>(t, stream);
-    case kTeam64x4:   return launch_cj<DT, BITS, ROUND, 64, 4>(t, stream);
-    case kTeam256x2:  return launch_cj<DT, BITS, ROUND, 256, 2>(t, stream);
-    case kTeam256x4:  return launch_cj<DT, BITS, ROUND, 256, 4>(t, stream);
-    case kTeam1024x2: return launch_cj<DT, BITS, ROUND, 1024, 2>(t, stream);
-    case kTeam1024x4: return launch_cj<DT, BITS, ROUND, 1024, 4>(t, stream);
+    case kTeam8x1:    return launch_cj<DT, ROUND, THREE, 8, 1>(t, stream);
+    case kTeam16x1:   return launch_cj<DT, ROUND, THREE, 16, 1>(t, stream);
+    case kTeam32x1:   return launch_cj<DT, ROUND, THREE, 32, 1>(t, stream);
+    case kTeam64x1:   return launch_cj<DT, ROUND, THREE, 64, 1>(t, stream);
+    case kTeam64x2:   return launch_cj<DT, ROUND, THREE, 64, 2>(t, stream);
+    case kTeam64x3:   return launch_cj<DT, ROUND, THREE, 64, 3>(t, stream);
+    case kTeam64x4:   return launch_cj<DT, ROUND, THREE, 64, 4>(t, stream);
+    case kTeam256x2:  return launch_cj<DT, ROUND, THREE, 256, 2>(t, stream);
+    case kTeam256x4:  return launch_cj<DT, ROUND, THREE, 256, 4>(t, stream);
+    case kTeam1024x2: return launch_cj<DT, ROUND, THREE, 1024, 2>(t, stream);
+    case kTeam1024x4: return launch_cj<DT, ROUND, THREE, 1024, 4>(t, stream);
     default:          return hipErrorInvalidValue;
     }
 }
 
-template <int DT, int BITS>
-static hipError_t launch_cj_round(int rounding, int shape, const JobTable& t, hipStream_t stream) {
-    return rounding == AQSGD_ROUND_STOCHASTIC
-               ? launch_cj_shape<DT, BITS, AQSGD_ROUND_STOCHASTIC>(shape, t, stream)
-               : launch_cj_shape<DT, BITS, AQSGD_ROUND_NEAREST>(shape, t, stream);
-}
-
 template <int DT>
-hipError_t launch_codec_jobs_dt(int bits, int rounding, int shape, const JobTable& t, hipStream_t stream) {
-    switch (bits) {
-    case 2: return launch_cj_round<DT, 2>(rounding, shape, t, stream);
-    case 3: return launch_cj_round<DT, 3>(rounding, shape, t, stream);
-    case 4: return launch_cj_round<DT, 4>(rounding, shape, t, stream);
-    case 6: return launch_cj_round<DT, 6>(rounding, shape, t, stream);
-    case 8: return launch_cj_round<DT, 8>(rounding, shape, t, stream);
-    default: return hipErrorInvalidValue;
-    }
+hipError_t launch_codec_jobs_dt(int rounding, int shape, bool three, const JobTable& t, hipStream_t stream) {
+    if (rounding == AQSGD_ROUND_STOCHASTIC)
+        return three ? launch_cj_shape<DT, AQSGD_ROUND_STOCHASTIC, true>(shape, t, stream)
+                     : launch_cj_shape<DT, AQSGD_ROUND_STOCHASTIC, false>(shape, t, stream);
+    return three ? launch_cj_shape<DT, AQSGD_ROUND_NEAREST, true>(shape, t, stream)
+                 : launch_cj_shape<DT, AQSGD_ROUND_NEAREST, false>(shape, t, stream);
 }
 
 template <int DT>
@@ -75,7 +65,7 @@ hipError_t launch_dequant_anyshape_dt(const DequantJob& a, hipStream_t stream) {
 }
 
 #define AQSGD_INSTANTIATE_DTYPE(DT)                                                               \
-    template hipError_t launch_codec_jobs_dt<DT>(int, int, int, const JobTable&, hipStream_t);    \
+    template hipError_t launch_codec_jobs_dt<DT>(int, int, bool, const JobTable&, hipStream_t);   \
     template hipError_t launch_dequant_jobs_dt<DT>(int, const JobTable&, hipStream_t);            \
     template hipError_t launch_quant_anyshape_dt<DT>(int, int, const QuantJob&, hipStream_t);     \
     template hipError_t launch_dequant_anyshape_dt<DT>(const DequantJob&, hipStream_t);

@@ -28,6 +28,7 @@
 
 #include <hip/hip_ext.h>
 
+#include <cstddef>
 #include <tuple>
 #include <utility>
 
@@ -59,8 +60,9 @@ struct QuantJob {
     int32_t batch;
     int32_t group;             // G
     int32_t cpg;               // chunks per group (G / 8), team kernels only
-    uint32_t block0;           // first workgroup of this job in the launch
+    int32_t bits;
     uint32_t grid_x, grid_y;   // its workgroups: grid_x per sample row, grid_y rows
+    float rcp_grid_x;          // 1 / grid_x, for the workgroup's position in that rectangle
     uint64_t seed;
     uint32_t* seen;            // or nullptr: no first-visit handling
     int32_t* first;            // with seen: first[i] = 1 if sample i was new, else 0
@@ -81,8 +83,8 @@ struct DequantJob {
     int32_t group;
     int32_t cpg;
     int32_t bits;
-    uint32_t block0;
     uint32_t grid_x, grid_y;
+    float rcp_grid_x;
     uint32_t* seen;            // or nullptr
     uint32_t stamp;
 };
@@ -90,10 +92,18 @@ struct DequantJob {
 constexpr int kMaxQuantJobs = 8;       // per launch
 constexpr int kMaxDequantJobs = 8;
 
+// The table is the kernel's argument.  A wave's first instructions fetch it from
+// memory, and every fetch that depends on an earlier one adds its full latency to the
+// start of every workgroup of the first wave of a launch.  So everything needed to
+// find a workgroup's job sits in the header at fixed offsets, next to the first job
+// of each kind, which is read at fixed offsets too; only a workgroup of a later job
+// reads its job through a computed offset.
 struct JobTable {
     int32_t n_quant, n_dequant;
     uint32_t dequant_block0;           // workgroups below this number belong to quantising jobs
     uint32_t total_blocks;
+    uint32_t q_block0[kMaxQuantJobs];  // first workgroup of each job, ascending
+    uint32_t d_block0[kMaxDequantJobs];
     QuantJob q[kMaxQuantJobs];
     DequantJob d[kMaxDequantJobs];
 };
@@ -519,37 +529,115 @@ __device__ __forceinline__ void dequant_job(const DequantJob& a, uint32_t bx, ui
     }
 }
 
-// Workgroup number -> (job, position in the job's rectangle).  Jobs are listed in
-// ascending order of their first workgroup; everything here is uniform.
-template <typename Job>
-__device__ __forceinline__ int job_of_block(const Job* jobs, int n, uint32_t b) {
+// The compiler fetches a kernel argument where it is first used, behind whatever
+// branch that is, and keeping a whole job in registers from the top would cost more
+// registers than the kernels can spare.  A chain of such fetches, each missing the
+// scalar cache, would open every workgroup of a launch's first wave.  touch_lines()
+// reads one word of each 64-byte line that such a workgroup is going to need, all in
+// one batch, so the misses overlap and the later fetches hit the cache.
+__device__ __forceinline__ void touch_lines(const void* base, int first_byte, int last_byte) {
+    const char* p = static_cast<const char*>(base);
+    const int l0 = first_byte / 64, l1 = last_byte / 64;       // constants after inlining
+    uint32_t w0 = *reinterpret_cast<const uint32_t*>(p + 64 * l0);
+    uint32_t w1 = *reinterpret_cast<const uint32_t*>(p + 64 * (l0 + 1 <= l1 ? l0 + 1 : l1));
+    uint32_t w2 = *reinterpret_cast<const uint32_t*>(p + 64 * (l0 + 2 <= l1 ? l0 + 2 : l1));
+    uint32_t w3 = *reinterpret_cast<const uint32_t*>(p + 64 * (l0 + 3 <= l1 ? l0 + 3 : l1));
+    asm volatile("" : : "s"(w0), "s"(w1), "s"(w2), "s"(w3));
+}
+static_assert(sizeof(QuantJob) <= 192 && sizeof(DequantJob) <= 192, "touch_lines covers four lines");
+
+struct BlockStarts { u32x4_t lo, hi; };                  // first workgroup of jobs 0..3, 4..7
+static_assert(kMaxQuantJobs == 8 && kMaxDequantJobs == 8, "BlockStarts holds eight");
+
+__device__ __forceinline__ BlockStarts block_starts(const uint32_t (&b)[8]) {
+    BlockStarts s;
+    s.lo = u32x4_t{b[0], b[1], b[2], b[3]};
+    s.hi = u32x4_t{b[4], b[5], b[6], b[7]};
+    return s;
+}
+
+// Workgroup number -> job from the first-workgroup numbers (ascending).
+__device__ __forceinline__ int job_of_block(const BlockStarts& s, int n, uint32_t b) {
     int j = 0;
-    for (int k = 1; k < n; ++k)
-        if (b >= jobs[k].block0) j = k;
+#pragma unroll
+    for (int k = 1; k < 8; ++k) {
+        const uint32_t start = k < 4 ? s.lo[k] : s.hi[k - 4];
+        if (k < n && b >= start) j = k;
+    }
     return j;
+}
+
+__device__ __forceinline__ uint32_t start_of_job(const BlockStarts& s, int j) {
+    uint32_t v = s.lo[0];
+#pragma unroll
+    for (int k = 1; k < 8; ++k)
+        if (j == k) v = k < 4 ? s.lo[k] : s.hi[k - 4];
+    return v;
+}
+
+// Position of workgroup `local` in a job's grid_x x grid_y rectangle (local < 2^24).
+__device__ __forceinline__ void place_in_job(uint32_t local, uint32_t grid_x, float rcp_grid_x, uint32_t& bx,
+                                             uint32_t& by) {
+    uint32_t y = static_cast<uint32_t>(static_cast<float>(local) * rcp_grid_x);
+    if (y * grid_x > local) --y;
+    else if ((y + 1) * grid_x <= local) ++y;
+    by = y;
+    bx = local - y * grid_x;
 }
 
 constexpr int kHostedDequantUnroll = 2;      // dequantising jobs inside a quantising kernel's launch
 
-// The quantising jobs of one kernel configuration plus any dequantising jobs.
+// One quantising job in a team kernel: the body for its bit width and for with /
+// without previous messages.  The 3-bit bodies (codes leave through a lane
+// transpose) need a sixth more registers than the others, which would cost every
+// launch a wave of occupancy per SIMD, so they live in a kernel of their own:
+// THREE selects between the bodies for 3 bits and those for 2, 4, 6 and 8.
 template <int DT, int BITS, int ROUND, int TEAM, int CPL>
+__device__ __forceinline__ void quant_job_bits(const QuantJob& a, uint32_t bx, uint32_t by, float* wave_max) {
+    if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, bx, by, wave_max);
+    else quant_team_body<DT, BITS, ROUND, TEAM, CPL, false>(a, bx, by, wave_max);
+}
+
+template <int DT, int ROUND, int TEAM, int CPL, bool THREE>
+__device__ __forceinline__ void quant_job(const QuantJob& a, uint32_t bx, uint32_t by, float* wave_max) {
+    if constexpr (THREE) {
+        quant_job_bits<DT, 3, ROUND, TEAM, CPL>(a, bx, by, wave_max);
+    } else {
+        switch (a.bits) {                                // uniform over the workgroup
+        case 2: quant_job_bits<DT, 2, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+        case 4: quant_job_bits<DT, 4, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+        case 6: quant_job_bits<DT, 6, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+        default: quant_job_bits<DT, 8, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+        }
+    }
+}
+
+// The quantising jobs of one rounding mode, team shape and bit-width class (3 bits, or
+// any of the others) plus any dequantising jobs.
+template <int DT, int ROUND, int TEAM, int CPL, bool THREE>
 __global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
 void codec_jobs_kernel(const JobTable t) {
     constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     static_assert(TEAM <= kWave || TEAM == kThreads, "a multi-wave team is the whole workgroup");
     [[maybe_unused]] __shared__ float wave_max[kThreads / kWave];
     const uint32_t b = blockIdx.x;
+    // header (job counts, first workgroups) and the first quantising job: the workgroups
+    // of a launch's first wave belong to it
+    touch_lines(&t, 0, 63);
+    touch_lines(&t, offsetof(JobTable, q), offsetof(JobTable, q) + sizeof(QuantJob) - 1);
+    uint32_t bx, by;
     if (b < t.dequant_block0) {
-        const QuantJob& a = t.q[job_of_block(t.q, t.n_quant, b)];
-        const uint32_t local = b - a.block0;
-        const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
-        if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, bx, by, wave_max);
-        else quant_team_body<DT, BITS, ROUND, TEAM, CPL, false>(a, bx, by, wave_max);
+        const BlockStarts qs = block_starts(t.q_block0);
+        const int j = job_of_block(qs, t.n_quant, b);
+        const QuantJob& a = t.q[j];
+        place_in_job(b - start_of_job(qs, j), a.grid_x, a.rcp_grid_x, bx, by);
+        quant_job<DT, ROUND, TEAM, CPL, THREE>(a, bx, by, wave_max);
     } else {
-        const DequantJob& a = t.d[job_of_block(t.d, t.n_dequant, b)];
-        const uint32_t local = b - a.block0;
-        const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
-        dequant_job<DT, kHostedDequantUnroll, kThreads>(a, bx, by);
+        const BlockStarts ds = block_starts(t.d_block0);
+        const int j = job_of_block(ds, t.n_dequant, b);
+        const DequantJob& d = t.d[j];
+        place_in_job(b - start_of_job(ds, j), d.grid_x, d.rcp_grid_x, bx, by);
+        dequant_job<DT, kHostedDequantUnroll, kThreads>(d, bx, by);
     }
 }
 
@@ -558,9 +646,13 @@ template <int DT, int UNROLL>
 __global__ __launch_bounds__(kBlock)
 void dequant_jobs_kernel(const JobTable t) {
     const uint32_t b = blockIdx.x;
-    const DequantJob& a = t.d[job_of_block(t.d, t.n_dequant, b)];
-    const uint32_t local = b - a.block0;
-    const uint32_t by = local / a.grid_x, bx = local - by * a.grid_x;
+    touch_lines(&t, 0, 63);
+    touch_lines(&t, offsetof(JobTable, d), offsetof(JobTable, d) + sizeof(DequantJob) - 1);
+    const BlockStarts ds = block_starts(t.d_block0);
+    const int j = job_of_block(ds, t.n_dequant, b);
+    const DequantJob& a = t.d[j];
+    uint32_t bx, by;
+    place_in_job(b - start_of_job(ds, j), a.grid_x, a.rcp_grid_x, bx, by);
     dequant_job<DT, UNROLL, kBlock>(a, bx, by);
 }
 
@@ -732,16 +824,17 @@ enum TeamShape {
     kTeam256x2, kTeam256x4, kTeam1024x2, kTeam1024x4, kNumTeamShapes
 };
 
-// A launch of codec_jobs_kernel (the table's quantising jobs all have this bit width,
-// rounding mode and team shape) or, with no quantising job, of dequant_jobs_kernel.
-hipError_t launch_codec_jobs(int dtype, int bits, int rounding, int shape, const JobTable& t,
+// A launch of codec_jobs_kernel (the table's quantising jobs all have this rounding
+// mode and team shape, and are either all 3-bit or all not) or, with no quantising job,
+// of dequant_jobs_kernel.
+hipError_t launch_codec_jobs(int dtype, int rounding, int shape, bool three, const JobTable& t,
                              hipStream_t stream);
 hipError_t launch_dequant_jobs(int dtype, int unroll, const JobTable& t, hipStream_t stream);
 hipError_t launch_quant_anyshape(int dtype, int bits, int rounding, const QuantJob& a, hipStream_t stream);
 hipError_t launch_dequant_anyshape(int dtype, const DequantJob& a, hipStream_t stream);
 
 // Per-dtype pieces (defined by AQSGD_INSTANTIATE_DTYPE in the dtype's .hip file).
-template <int DT> hipError_t launch_codec_jobs_dt(int bits, int rounding, int shape, const JobTable& t,
+template <int DT> hipError_t launch_codec_jobs_dt(int rounding, int shape, bool three, const JobTable& t,
                                                   hipStream_t stream);
 template <int DT> hipError_t launch_dequant_jobs_dt(int unroll, const JobTable& t, hipStream_t stream);
 template <int DT> hipError_t launch_quant_anyshape_dt(int bits, int rounding, const QuantJob& a,

@@ -1,8 +1,10 @@
-"""Parity in the launch configuration that bench.py times: the GPT2-1.5B-shaped
+"""Parity in the launch configurations that bench.py times: the GPT2-1.5B-shaped
 boundary at full size (8192-sample buffers, float16 [4, 1024, 1600] micro-batches),
-steps recorded into a HIP graph with the forward pairs dealt over two streams and the
-backward pairs over two more, replayed twice.  Every output of every step, and every
-visited row of both copies of m, must equal the oracle's after each replay."""
+steps recorded into a HIP graph with bench.py's own enqueueing code and replayed twice:
+the default (one launch per time slot of the two stages, micro-batches dealt over two
+streams), the per-stage launches, and the four single calls on four streams.  Every
+output of every step, and every visited row of both copies of m, must equal the oracle's
+after each replay."""
 import numpy as np
 import pytest
 import torch
@@ -13,7 +15,8 @@ from paper_2206_01299_amd import binding as B
 from paper_2206_01299_amd import workloads as W
 
 
-def test_graph_on_four_streams_at_full_size_matches_the_oracle():
+@pytest.mark.parametrize("schedule,n_streams", [("pipeline", 2), ("stage", 2), ("calls", 4), ("pipeline", 1)])
+def test_graph_at_full_size_matches_the_oracle(schedule, n_streams):
     if not torch.cuda.is_available():
         pytest.fail("needs the MI355X")
     B.lib()
@@ -22,20 +25,12 @@ def test_graph_on_four_streams_at_full_size_matches_the_oracle():
     cfg = W.gpt2_4bit()
     steps = 8
     wl = bench.Workload(cfg, pool=steps)                 # m starts at zero: replay 1 = first visits
-    wl.make_streams(4)
+    if n_streams > 1:
+        wl.make_streams(n_streams)
     main = torch.cuda.Stream()
     graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=main):           # the enqueue pattern of bench.timed_steps
-        fork = torch.cuda.Event()
-        fork.record(main)
-        for st in wl.streams:
-            st.wait_event(fork)
-        for k in range(steps):
-            wl.step_on_streams(k)
-        for st in wl.streams:
-            done = torch.cuda.Event()
-            done.record(st)
-            main.wait_event(done)
+    with torch.cuda.graph(graph, stream=main):           # the enqueueing code of bench.timed_steps
+        bench.enqueue_steps(wl, main, 0, steps, n_streams, schedule)
     torch.cuda.synchronize()
     assert not bool(wl.m_send[wl.ids[0]].any())          # capture ran nothing
 
