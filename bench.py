@@ -100,6 +100,14 @@ def parse_args():
     ap.add_argument("--bwd-keep", type=float, default=0.0,
                     help="sparsify the backward message (Appendix H.6): fraction of each group's "
                          "entries that is sent, at 8 bits; 0 = dense (the headline configuration)")
+    ap.add_argument("--first-visit", action="store_true",
+                    help="secondary line: Algorithm 1's uncompressed first visits (aqsgd_seed, "
+                         "aqsgd_encode_seen / aqsgd_decode_seen on new samples) against a same-run copy "
+                         "of the same size, then the second visits through the same entry points")
+    ap.add_argument("--ceilings", action="store_true",
+                    help="secondary line: what this GPU does with launches of this size: a near-empty "
+                         "launch, the library's plain row copy and its encode / decode at growing "
+                         "micro-batch sizes, and large fill / copy kernels")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
                          "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
@@ -621,6 +629,193 @@ def read_traffic():
     return vals or None
 
 
+def isolated_launches(torch, B, count, launch):
+    """Average device duration (us) of `count` single launches made by launch(i), each
+    stamped by the library's timed-launch hook on its own stream."""
+    pairs = []
+    for _ in range(count):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(); b.record()
+        pairs.append((a, b))
+    for i in range(count, count + 24):                   # untimed: clocks and caches in their working state
+        launch(i)
+    torch.cuda.synchronize()
+    for i, (a, b) in enumerate(pairs):
+        B.profile_next_launch(a, b)
+        launch(i)
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in pairs)
+    return {"avg_us": round(1e3 * sum(ms) / len(ms), 3), "median_us": round(1e3 * ms[len(ms) // 2], 3),
+            "min_us": round(1e3 * ms[0], 3), "launches": count}
+
+
+def torch_copy_us(torch, src_pool, dst_pool, reps):
+    """A plain device-to-device copy of one pool slot per launch, cold rotating slots (us)."""
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    n = src_pool.shape[0]
+    for i in range(4):
+        dst_pool[i % n].copy_(src_pool[i % n])
+    torch.cuda.synchronize()
+    a.record()
+    for i in range(reps):
+        dst_pool[i % n].copy_(src_pool[(i + n // 2) % n])
+    b.record()
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) * 1e3 / reps
+
+
+def first_visit_line(args, cfg, wl):
+    """Algorithm 1's first-visit branch: one epoch in which every sample is new (the message
+    is the activation itself, both stages store it as m), then the same calls again (every
+    sample seen: the ordinary codec path through the same entry points)."""
+    torch, B = wl.torch, wl.B
+    d = wl.dev
+    n_calls = min(wl.calls, max(64, args.steps))
+    seen_s = torch.zeros(cfg.n_samples, dtype=torch.int32, device=d)
+    seen_r = torch.zeros_like(seen_s)
+    first = torch.zeros((wl.pool, cfg.batch), dtype=torch.int32, device=d)
+    wl.m_send.zero_(); wl.m_recv.zero_()
+    act_bytes = cfg.n * cfg.elem_bytes
+    lb = wl.leg_bytes()
+
+    def enc(k, stamp):
+        s = k % wl.pool
+        B.encode_seen(wl.fdesc, wl.act[s], wl.ids[k % wl.calls], wl.m_send, seen_s, stamp, first[s],
+                      wl.codes[s], wl.scales[s])
+
+    def dec(k, stamp):
+        s = k % wl.pool            # on a first visit the uncompressed rows are the message
+        B.decode_seen(wl.fdesc, wl.codes[s], wl.scales[s], wl.act[s], wl.ids[k % wl.calls], wl.m_recv, seen_r,
+                      stamp, wl.out[s])
+
+    res = {}
+    res["encode_seen_first"] = isolated_launches(torch, B, n_calls, lambda i: enc(i, 1 + i))
+    res["decode_seen_first"] = isolated_launches(torch, B, n_calls, lambda i: dec(i, 1 + i))
+    assert int((seen_s != 0).sum()) == n_calls * cfg.batch and bool((seen_s != 0).eq(seen_r != 0).all())
+    assert bool(torch.equal(wl.m_send, wl.m_recv))
+    res["encode_seen_second"] = isolated_launches(torch, B, n_calls, lambda i: enc(i, 100000 + i))
+    res["decode_seen_second"] = isolated_launches(torch, B, n_calls, lambda i: dec(i, 100000 + i))
+    assert bool(torch.equal(wl.m_send, wl.m_recv))
+    res["seed"] = isolated_launches(
+        torch, B, n_calls, lambda i: B.seed(wl.fdesc, wl.act[i % wl.pool], wl.ids[i % wl.calls], wl.m_send))
+    # the same copies through the runtime's own copy kernel, same size, cold slots
+    copy_us = torch_copy_us(torch, wl.act, wl.out, n_calls)
+    bytes_of = {"encode_seen_first": 2 * act_bytes, "decode_seen_first": 3 * act_bytes, "seed": 2 * act_bytes,
+                "encode_seen_second": lb["encode"], "decode_seen_second": lb["decode"]}
+    for k, v in res.items():
+        v["bytes"] = bytes_of[k]
+        v["hbm_GBps"] = round(bytes_of[k] / v["avg_us"] / 1e3, 1)
+        v["frac_of_hbm_peak"] = round(bytes_of[k] / v["avg_us"] / 1e3 / HBM_PEAK_GBPS, 4)
+
+    # the whole first epoch as a pipeline would run it: sender and receiver alternate on one
+    # stream; device time by events around a graph replay
+    wl.m_send.zero_(); wl.m_recv.zero_(); seen_s.zero_(); seen_r.zero_()
+    main = torch.cuda.Stream()
+    clock = DeviceClock(torch, main)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=main):
+        for k in range(n_calls):
+            enc(k, 1 + k)
+            dec(k, 1 + k)
+    dev_first, _ = clock.time(g.replay)          # every sample new (the graph's first replay)
+    dev_second, _ = clock.time(g.replay)         # same stamps again: the samples count as new once more
+    pair_first = dev_second / n_calls
+    copy_ceiling = 2 * act_bytes / (copy_us * 1e-6) / 1e9
+    seed_gbps = res["seed"]["hbm_GBps"]
+    line = {
+        "metric": "first-visit path (uncompressed message, m <- a on both stages) GB/s against a same-run "
+                  "copy of the same size",
+        "value": round(seed_gbps, 1), "unit": "GB/s", "n_gpus": 1, "steps": n_calls, "warmup": 0,
+        "ms_per_step": round(pair_first * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.config] + "; first epoch: every sample new",
+                   "value_is": "read + written bytes per second of aqsgd_seed (m_buf[ids] <- act), isolated "
+                               "launches on cold rows",
+                   "step": "aqsgd_encode_seen + aqsgd_decode_seen of one micro-batch of new samples "
+                           "(ms_per_step: back to back on one stream, second replay of the graph)"},
+        "seed_vs_copy": {"seed_GBps": seed_gbps, "copy_same_size_GBps": round(copy_ceiling, 1),
+                         "ratio": round(seed_gbps / copy_ceiling, 3),
+                         "copy_1GiB_GBps": round(stream_copy_ceiling(torch), 1)},
+        "first_replay_us_per_pair": round(dev_first / n_calls * 1e6, 3),
+        "launches": res, "roofline": {"bound": "hbm", "kernel": "seed", "achieved": seed_gbps,
+                                      "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                                      "frac": round(seed_gbps / HBM_PEAK_GBPS, 4), "traffic": None},
+        "cpu_baseline": None,
+    }
+    print(json.dumps(line))
+
+
+def ceilings_line(args, cfg, wl):
+    """What launches of the codec's size can reach on this GPU, measured with the library's
+    own kernels and the runtime's fill / copy: the fixed cost of a launch, and how the
+    achieved bandwidth grows with the bytes per launch."""
+    torch, B = wl.torch, wl.B
+    d = wl.dev
+    out = {}
+    flag = torch.zeros(1, dtype=torch.int32, device=d)
+    one_id = torch.zeros(1, dtype=torch.int64, device=d)
+    out["near_empty_launch"] = isolated_launches(
+        torch, B, 256, lambda i: B.check_ids(one_id, cfg.n_samples, flag))
+    td = B.DTYPE_NAME[cfg.dtype]
+    rows = 64                                    # a pool of 64-row micro-batches for the size sweep
+    n_big = max(2, min(6, wl.pool * cfg.batch // rows))
+    act = wl.act.view(-1, cfg.n_per)
+    outp = wl.out.view(-1, cfg.n_per)
+    perm = torch.randperm(cfg.n_samples, device=d)
+    table = []
+    for b in (1, 2, 4, 8, 16, 32, 64):
+        if b * 8 > act.shape[0]:
+            break
+        desc = B.make_desc(batch=b, n_per=cfg.n_per, n_samples=cfg.n_samples, bits=cfg.fwd_bits,
+                           group=cfg.fwd_group, dtype=cfg.dtype, rounding=cfg.fwd_rounding)
+        codes = torch.empty((8, B.codes_bytes(desc)), dtype=torch.uint8, device=d)
+        scales = torch.empty((8, B.scales_count(desc)), dtype=torch.float32, device=d)
+        slots = act.shape[0] // b
+        calls = cfg.n_samples // b
+        reps = max(16, min(256, 4096 // b))
+
+        def a_of(i): return act[(i % slots) * b:(i % slots + 1) * b]
+        def o_of(i): return outp[(i % slots) * b:(i % slots + 1) * b]
+        def ids_of(i): return perm[(i % calls) * b:(i % calls + 1) * b]
+        row = {"batch": b, "bytes_encode": b * cfg.n_per * (3 * cfg.elem_bytes + cfg.fwd_bits / 8) +
+                                           4.0 * b * cfg.n_per / cfg.fwd_group}
+        row["seed_us"] = isolated_launches(torch, B, reps, lambda i: B.seed(desc, a_of(i), ids_of(i),
+                                                                            wl.m_send))["avg_us"]
+        row["encode_us"] = isolated_launches(torch, B, reps, lambda i: B.encode(
+            desc, a_of(i), ids_of(i), wl.m_send, codes[i % 8], scales[i % 8]))["avg_us"]
+        row["decode_us"] = isolated_launches(torch, B, reps, lambda i: B.decode(
+            desc, codes[i % 8], scales[i % 8], ids_of(i), wl.m_recv, o_of(i)))["avg_us"]
+        copy_bytes = 2.0 * b * cfg.n_per * cfg.elem_bytes
+        row["seed_GBps"] = round(copy_bytes / row["seed_us"] / 1e3, 1)
+        row["encode_GBps"] = round(row["bytes_encode"] / row["encode_us"] / 1e3, 1)
+        row["decode_GBps"] = round(row["bytes_encode"] / row["decode_us"] / 1e3, 1)
+        table.append(row)
+    out["launch_size_sweep"] = table
+    big = torch.empty(1 << 29, dtype=torch.float16, device=d)
+    big2 = torch.empty_like(big)
+    a, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    big.fill_(1.0); big2.copy_(big); torch.cuda.synchronize()
+    a.record()
+    for _ in range(5):
+        big.fill_(2.0)
+    b_.record(); torch.cuda.synchronize()
+    out["fill_1GiB_GBps"] = round((1 << 30) * 5 / (a.elapsed_time(b_) * 1e-3) / 1e9, 1)
+    out["copy_1GiB_GBps"] = round(stream_copy_ceiling(torch), 1)
+    seed64 = table[-1]
+    line = {
+        "metric": "ceilings of this GPU at the codec's launch sizes (GB/s of read + written bytes)",
+        "value": seed64["seed_GBps"], "unit": "GB/s", "n_gpus": 1, "steps": 0, "warmup": 0,
+        "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.config] + "; launch-size sweep",
+                   "value_is": f"the library's row copy (aqsgd_seed) at {seed64['batch']} rows per launch",
+                   "method": "every figure is the average device duration of isolated launches on cold rows, "
+                             "stamped by HIP events on the launching stream"},
+        "ceilings": out, "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -655,6 +850,13 @@ def main():
             dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+
+    if args.first_visit:
+        first_visit_line(args, cfg, wl)
+        return
+    if args.ceilings:
+        ceilings_line(args, cfg, wl)
+        return
 
     for k in range(Wm):                                  # untimed warm-up, eager
         wl.step(k)

@@ -73,7 +73,8 @@ typedef enum {
     AQSGD_ERR_DTYPE = -4,     /* unknown dtype or rounding mode                     */
     AQSGD_ERR_SHAPE = -5,     /* negative or overflowing batch / n_per / n_samples  */
     AQSGD_ERR_ALIGN = -6,     /* a pointer misses its alignment                     */
-    AQSGD_ERR_LAUNCH = -7     /* the HIP runtime refused the launch                 */
+    AQSGD_ERR_LAUNCH = -7,    /* the HIP runtime refused the launch                 */
+    AQSGD_ERR_IO = -8         /* file tier: open / read / write failed              */
 } aqsgd_status;
 
 /* Shape and settings of one call (host memory). */
@@ -279,37 +280,59 @@ int aqsgd_grad_topk_dequant(const aqsgd_desc* desc, int32_t keep, const uint8_t*
                             const uint8_t* codes, const float* scales, void* out, void* stream);
 
 /*
- * Host-memory tier for the previous messages (the implementation notes of Section 3.3
- * and Appendix G: m(xi) lives in host memory, is brought to the GPU before the forward
- * pass of its sample and goes back after the update, both behind the computation of
- * other samples).
+ * Tiers below HBM for the previous messages (the implementation notes of Section 3.3
+ * and Appendix G: m(xi) lives in host memory or on an SSD, is brought to the GPU before
+ * the forward pass of its sample and goes back after the update, both behind the
+ * computation of other samples).
  *
- * All N rows live in PINNED HOST memory; HBM holds `slots` windows of `batch` rows.
- * A micro-batch's rows are copied into a window ahead of time on a copy stream
- * (prefetch), the codec runs on the window with the window's row numbers as its
- * sample ids (acquire), and the updated rows go back afterwards (release).  Memory is
- * the caller's: host_rows [n_samples, row_bytes] pinned (hipHostMalloc / a pinned
- * tensor), dev_rows [slots*batch, row_bytes] and dev_row_ids int64 [slots*batch] on the
- * device.  The tier object only holds the events that order the two streams, plus
- * which samples each window holds.  Calls on one tier must come from one host thread.
+ * HBM holds `slots` windows of `batch` rows.  A micro-batch's rows are brought into a
+ * window ahead of time (prefetch), the codec runs on the window with the window's row
+ * numbers as its sample ids (acquire), and the updated rows go back afterwards (release).
+ * The tier object is the stateful part of this library: it owns HIP events, which samples
+ * each window holds and, for the file tier, a file descriptor and a worker thread.  It
+ * never owns data memory: dev_rows [slots*batch, row_bytes] and dev_row_ids int64
+ * [slots*batch] are the caller's device memory, the host memory below the caller's pinned
+ * host memory (hipHostMalloc / a pinned tensor).  Calls on one tier must come from one host
+ * thread, and every call that takes a copy stream must name the same one (the order of
+ * its copies keeps a write-back ahead of a later prefetch of the same window or sample;
+ * another stream is refused with AQSGD_ERR_SHAPE).
  *
- *   create    fills dev_row_ids with 0 .. slots*batch-1 (synchronously) and creates events
- *   prefetch  window <- host rows of host_ids (HOST int64[batch], distinct), on copy_stream;
+ *   aqsgd_tier_create       host tier: host_rows [n_samples, row_bytes] pinned holds every row
+ *   aqsgd_tier_create_file  file tier: the rows live in the file `path` (created or extended to
+ *                           n_samples * row_bytes; bytes never written read as zeros, Algorithm
+ *                           1's initial m); staging_rows [slots*batch, row_bytes] pinned is the
+ *                           only host memory.  A worker thread reads a window's rows into the
+ *                           staging rows and issues their copy to the device (read-ahead: up to
+ *                           `slots` windows ahead of the compute), and writes released rows back
+ *                           once they have arrived from the device (write-behind).  direct_io != 0
+ *                           opens the file unbuffered (O_DIRECT), which needs row_bytes to be a
+ *                           multiple of 4096 (else AQSGD_ERR_ALIGN); the tier then also owns one
+ *                           window of ordinary host memory, through which the file transfers
+ *                           pass (the kernel cannot do unbuffered I/O on pinned GPU-visible pages).
+ *   both fill dev_row_ids with 0 .. slots*batch-1 (synchronously) and create the events
+ *   prefetch  window <- rows of host_ids (HOST int64[batch], distinct), on copy_stream;
  *             a window must be released before it is prefetched again, and a sample that
  *             sits in an unreleased window cannot be prefetched (its newest row is in that
- *             window, not in host memory): both are refused with AQSGD_ERR_SHAPE
- *   acquire   makes compute_stream wait for the window's rows; returns the sample_ids
+ *             window, not below): both are refused with AQSGD_ERR_SHAPE.  If a copy cannot
+ *             be issued the window stays empty
+ *   acquire   makes compute_stream wait for the window's rows (file tier: first blocks the
+ *             host until the worker has read them from the file); returns the sample_ids
  *             pointer (device, batch entries) to pass to the codec with m_buf = dev_rows,
  *             n_samples = slots*batch
- *   release   after the codec calls queued so far on compute_stream, copies the window's
- *             rows back to their host rows on copy_stream
- *   drain     blocks until every copy issued so far has finished (host rows are current)
- * Return: AQSGD_OK, AQSGD_ERR_NULL / _SHAPE for bad arguments, AQSGD_ERR_LAUNCH if the
- * HIP runtime fails.
+ *   release   after the codec calls queued so far on compute_stream, sends the window's
+ *             rows back on copy_stream (file tier: and from the staging rows to the file)
+ *   drain     blocks until every copy and file transfer issued so far has finished
+ *   destroy   drains, stops the worker, closes the file, destroys the events
+ * Return: AQSGD_OK, AQSGD_ERR_NULL / _SHAPE / _ALIGN for bad arguments, AQSGD_ERR_LAUNCH if
+ * the HIP runtime fails, AQSGD_ERR_IO if the file cannot be opened, sized, read or written
+ * (a failure inside the worker is reported by the next acquire, release, prefetch or drain).
  */
 typedef struct aqsgd_tier aqsgd_tier;
 int aqsgd_tier_create(aqsgd_tier** tier, void* host_rows, void* dev_rows, int64_t* dev_row_ids,
                       int64_t n_samples, int64_t row_bytes, int32_t slots, int32_t batch);
+int aqsgd_tier_create_file(aqsgd_tier** tier, const char* path, int32_t direct_io, void* staging_rows,
+                           void* dev_rows, int64_t* dev_row_ids, int64_t n_samples,
+                           int64_t row_bytes, int32_t slots, int32_t batch);
 int aqsgd_tier_prefetch(aqsgd_tier* tier, int32_t slot, const int64_t* host_ids, void* copy_stream);
 int aqsgd_tier_acquire(aqsgd_tier* tier, int32_t slot, void* compute_stream,
                        const int64_t** sample_ids);

@@ -27,7 +27,8 @@ DTYPE_NAME = {"f32": torch.float32, "f16": torch.float16, "bf16": torch.bfloat16
 EXPORTS = ("aqsgd_codes_bytes", "aqsgd_scales_count", "aqsgd_encode", "aqsgd_decode",
            "aqsgd_grad_quant", "aqsgd_grad_dequant", "aqsgd_run_jobs", "aqsgd_seed", "aqsgd_encode_seen",
            "aqsgd_decode_seen", "aqsgd_lowbit_row_bytes",
-           "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_prefetch",
+           "aqsgd_encode_lowbit", "aqsgd_decode_lowbit", "aqsgd_tier_create", "aqsgd_tier_create_file",
+           "aqsgd_tier_prefetch",
            "aqsgd_tier_acquire", "aqsgd_tier_release", "aqsgd_tier_drain", "aqsgd_tier_destroy",
            "aqsgd_topk_bitmap_bytes", "aqsgd_topk_codes_bytes", "aqsgd_grad_topk_quant",
            "aqsgd_grad_topk_dequant", "aqsgd_check_ids", "aqsgd_set_launch_shape",
@@ -107,6 +108,9 @@ def lib() -> ctypes.CDLL:
         L.aqsgd_tier_create.restype = ctypes.c_int
         L.aqsgd_tier_create.argtypes = [ctypes.POINTER(vp), vp, vp, vp, ctypes.c_int64, ctypes.c_int64,
                                         ctypes.c_int32, ctypes.c_int32]
+        L.aqsgd_tier_create_file.restype = ctypes.c_int
+        L.aqsgd_tier_create_file.argtypes = [ctypes.POINTER(vp), ctypes.c_char_p, ctypes.c_int32, vp, vp, vp,
+                                             ctypes.c_int64, ctypes.c_int64, ctypes.c_int32, ctypes.c_int32]
         L.aqsgd_tier_prefetch.restype = ctypes.c_int
         L.aqsgd_tier_prefetch.argtypes = [vp, ctypes.c_int32, vp, vp]
         L.aqsgd_tier_acquire.restype = ctypes.c_int
@@ -404,23 +408,38 @@ def profile_next_launch(start: "torch.cuda.Event", stop: "torch.cuda.Event") -> 
 
 
 class Tier:
-    """Handle of ``aqsgd_tier``: previous messages in pinned host memory, ``slots``
-    windows of ``batch`` rows in HBM.  The three tensors are the caller's memory
-    (``host_rows`` pinned [N, row], ``dev_rows`` [slots*batch, row], ``dev_row_ids``
-    int64 [slots*batch]); this object only forwards calls and keeps them alive."""
+    """Handle of ``aqsgd_tier``: previous messages below HBM, ``slots`` windows of ``batch``
+    rows in HBM.  Host tier: ``host_rows`` pinned [N, row] holds every row.  File tier
+    (``path`` given): the rows live in that file and ``host_rows`` pinned [slots*batch, row]
+    is the staging memory; ``n_samples`` is then the number of rows of the file.  The
+    tensors are the caller's memory (``dev_rows`` [slots*batch, row], ``dev_row_ids`` int64
+    [slots*batch]); this object only forwards calls and keeps them alive."""
 
-    def __init__(self, host_rows, dev_rows, dev_row_ids, slots: int, batch: int):
+    def __init__(self, host_rows, dev_rows, dev_row_ids, slots: int, batch: int, path: str | None = None,
+                 n_samples: int | None = None, direct_io: bool = False):
         if not host_rows.is_pinned() or host_rows.is_cuda or not host_rows.is_contiguous():
             raise ValueError("host_rows must be a contiguous pinned host tensor")
         if dev_rows.shape[0] != slots * batch or dev_row_ids.numel() != slots * batch:
             raise ValueError("dev_rows / dev_row_ids must hold slots * batch rows")
+        if dev_row_ids.dtype != torch.int64:
+            raise ValueError("dev_row_ids must be int64")
         self.host_rows, self.dev_rows, self.dev_row_ids = host_rows, dev_rows, dev_row_ids
         self.slots, self.batch = slots, batch
         row_bytes = host_rows[0].numel() * host_rows.element_size()
+        if dev_rows[0].numel() * dev_rows.element_size() != row_bytes:
+            raise ValueError("host and device rows differ in size")
         self._h = ctypes.c_void_p()
-        _raise(lib().aqsgd_tier_create(ctypes.byref(self._h), ctypes.c_void_p(host_rows.data_ptr()),
-                                       _dev(dev_rows, "dev_rows"), _dev(dev_row_ids, "dev_row_ids"),
-                                       host_rows.shape[0], row_bytes, slots, batch))
+        if path is None:
+            _raise(lib().aqsgd_tier_create(ctypes.byref(self._h), ctypes.c_void_p(host_rows.data_ptr()),
+                                           _dev(dev_rows, "dev_rows"), _dev(dev_row_ids, "dev_row_ids"),
+                                           host_rows.shape[0], row_bytes, slots, batch))
+        else:
+            if host_rows.shape[0] != slots * batch or not n_samples:
+                raise ValueError("the file tier needs slots * batch staging rows and the file's row count")
+            _raise(lib().aqsgd_tier_create_file(ctypes.byref(self._h), str(path).encode(), int(direct_io),
+                                                ctypes.c_void_p(host_rows.data_ptr()), _dev(dev_rows, "dev_rows"),
+                                                _dev(dev_row_ids, "dev_row_ids"), n_samples, row_bytes, slots,
+                                                batch))
 
     def prefetch(self, slot: int, host_ids, copy_stream) -> None:
         """``host_ids``: host int64 tensor of ``batch`` distinct sample ids."""

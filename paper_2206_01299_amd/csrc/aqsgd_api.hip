@@ -697,9 +697,10 @@ const char* aqsgd_strerror(int status) {
     case AQSGD_ERR_BITS:   return "bits must be 2, 3, 4, 6 or 8";
     case AQSGD_ERR_GROUP:  return "group must be positive, divide n_per, and hold whole bytes of codes";
     case AQSGD_ERR_DTYPE:  return "unknown dtype or rounding mode";
-    case AQSGD_ERR_SHAPE:  return "batch / n_per / n_samples negative, zero or too large";
+    case AQSGD_ERR_SHAPE:  return "a size, count, stamp or slot is negative, zero, too large or out of turn";
     case AQSGD_ERR_ALIGN:  return "a pointer misses its required alignment";
     case AQSGD_ERR_LAUNCH: return "the HIP runtime refused the kernel launch";
+    case AQSGD_ERR_IO:     return "the file tier could not open, size, read or write its file";
     default:               return "unknown status";
     }
 }

@@ -102,6 +102,58 @@ def test_binding_has_no_cpu_route():
     assert "import oracle" not in src and "from oracle" not in src
 
 
+def test_binding_checks_tensor_types_and_sizes_against_the_descriptor(monkeypatch):
+    """The kernels index every buffer from the descriptor alone, so a tensor of another
+    element type or a smaller size must be refused before its pointer reaches the library
+    (an int32 id tensor would be read as int64: garbage rows, out-of-range writes)."""
+    import torch
+    monkeypatch.setattr(B, "_dev", lambda t, what: ctypes.c_void_p(0))    # host tensors stand in for device ones
+    d = B.make_desc(batch=2, n_per=64, n_samples=4, bits=4, group=64, dtype="f16")
+    act = torch.zeros((2, 64), dtype=torch.float16)
+    ids = torch.zeros(2, dtype=torch.int64)
+    m = torch.zeros((4, 64), dtype=torch.float16)
+    codes = torch.zeros(B.codes_bytes(d), dtype=torch.uint8)
+    scales = torch.zeros(B.scales_count(d), dtype=torch.float32)
+
+    def refused(what, **kw):
+        a = dict(act=act, sample_ids=ids, m_buf=m, codes=codes, scales=scales)
+        a.update(kw)
+        with pytest.raises(ValueError, match=what):
+            B.encode(d, a["act"], a["sample_ids"], a["m_buf"], a["codes"], a["scales"])
+
+    refused("sample_ids", sample_ids=ids.to(torch.int32))
+    refused("sample_ids", sample_ids=torch.zeros(3, dtype=torch.int64))
+    refused("act", act=act.float())
+    refused("act", act=torch.zeros((1, 64), dtype=torch.float16))
+    refused("m_buf", m_buf=torch.zeros((3, 64), dtype=torch.float16))
+    refused("m_buf", m_buf=m.to(torch.bfloat16))
+    refused("codes", codes=codes[:-1])
+    refused("codes", codes=codes.to(torch.int8))
+    refused("scales", scales=scales.double())
+    refused("scales", scales=scales[:-1])
+    with pytest.raises(ValueError, match="out"):
+        B.decode(d, codes, scales, ids, m, torch.zeros((2, 63), dtype=torch.float16))
+    with pytest.raises(ValueError, match="grad"):
+        B.grad_quant(d, act.to(torch.bfloat16), codes, scales)
+    with pytest.raises(ValueError, match="seen"):
+        B.encode_seen(d, act, ids, m, torch.zeros(4, dtype=torch.uint8), 1, torch.zeros(2, dtype=torch.int32),
+                      codes, scales)
+    with pytest.raises(ValueError, match="first"):
+        B.encode_seen(d, act, ids, m, torch.zeros(4, dtype=torch.int32), 1, torch.zeros(3, dtype=torch.int32),
+                      codes, scales)
+    with pytest.raises(ValueError, match="sample_ids"):
+        B.encode_job(d, act, ids.to(torch.int32), m, codes, scales)
+    # well-formed arguments pass the checks and reach the library (null pointers: refused there)
+    with pytest.raises(B.AqsgdError) as e:
+        B.encode(d, act, ids, m, codes, scales, stream=type("S", (), {"cuda_stream": 0})())
+    assert e.value.status == -1
+
+
+def test_job_layout_matches_header():
+    assert ctypes.sizeof(B.Job) == 8 + 48 + 6 * 8
+    assert B.Job.desc.offset == 8 and B.Job.src.offset == 56 and B.Job.out.offset == 96
+
+
 def test_header_is_plain_c_and_a_c_client_links(tmp_path):
     """The boundary is a C ABI: the header compiles as C99 on its own, and a C program
     that only knows the header links against the library and reads a size through it."""
@@ -120,12 +172,14 @@ def test_header_is_plain_c_and_a_c_client_links(tmp_path):
     src.write_text('#include <stdio.h>\n#include "aqsgd.h"\n'
                    'int main(void) {\n'
                    '    aqsgd_desc d = {4, 1638400, 8192, 4, 1600, AQSGD_F16, AQSGD_ROUND_NEAREST, 0};\n'
-                   '    printf("%zu %zu %s\\n", aqsgd_codes_bytes(&d), aqsgd_scales_count(&d), aqsgd_strerror(-3));\n'
+                   '    printf("%zu %zu %zu %s\\n", aqsgd_codes_bytes(&d), aqsgd_scales_count(&d), sizeof(aqsgd_job),\n'
+                   '           aqsgd_strerror(-3));\n'
                    '    return aqsgd_encode(&d, NULL, NULL, NULL, NULL, NULL, NULL) == AQSGD_ERR_NULL ? 0 : 1;\n'
                    '}\n')
     exe = tmp_path / "client"
     subprocess.run([gcc, "-std=c99", f"-I{header.parent}", str(src), str(lib), f"-Wl,-rpath,{lib.parent}",
                     "-Wl,-rpath,/opt/rocm/lib", "-o", str(exe)], check=True)
-    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=2)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True).stdout.split(maxsplit=3)
     assert out[0] == str(4 * 1638400 * 4 // 8) and out[1] == str(4 * 1638400 // 1600)
-    assert "group" in out[2]
+    assert int(out[2]) == ctypes.sizeof(B.Job)           # the binding's mirror of aqsgd_job has the C size
+    assert "group" in out[3]
