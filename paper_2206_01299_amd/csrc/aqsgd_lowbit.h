@@ -8,8 +8,8 @@
 //     sender:    Delta m = Q_b(a - m^)           -> codes, scales on the wire
 //     both:      v = m^ + Delta m  (binary32);   store Q_z(v), nearest rounding
 //     receiver:  out = dtype(v)
-// One team of lanes owns a group, as in quant_team_kernel, and runs two max
-// reductions: over |a - m^| for the wire scale and over |v| for the storage
+// One team of lanes owns a group, as in the plain quantising kernel, and runs two
+// max reductions: over |a - m^| for the wire scale and over |v| for the storage
 // scale.  Everything between the loads and the stores stays in registers.
 #pragma once
 
@@ -50,7 +50,38 @@ __device__ __forceinline__ float team_max_all(float mx, float* wave_max) {
     return mx;
 }
 
-template <int DT, int BITS, int MBITS, int TEAM, int CPL, bool SENDER>
+// Tells the compiler nothing about a packed word's value from here on, so that what is
+// derived from it afterwards is computed afresh instead of being kept in registers.
+__device__ __forceinline__ void forget(uint64_t& w) {
+    uint32_t lo = static_cast<uint32_t>(w), hi = static_cast<uint32_t>(w >> 32);
+    asm volatile("" : "+v"(lo), "+v"(hi));
+    w = (static_cast<uint64_t>(hi) << 32) | lo;
+}
+template <int DT>
+__device__ __forceinline__ void forget(Raw<DT>& r) {
+    if constexpr (DT == AQSGD_F32) {
+        asm volatile("" : "+v"(r.lo), "+v"(r.hi));
+    } else {
+        asm volatile("" : "+v"(r.v));
+    }
+}
+
+// m^ of one chunk from its stored levels.
+template <int MBITS>
+__device__ __forceinline__ void stored_values(uint64_t mw, const GroupScale& msc, float (&m)[kChunk]) {
+    float q[kChunk];
+    unpack_levels<MBITS>(mw, q);
+#pragma unroll
+    for (int e = 0; e < kChunk; ++e) m[e] = value_of(q[e], msc);
+}
+
+// One group.  The kernel is bound by vector arithmetic, not by memory (two quantisers and
+// a dequantiser per element), so nothing is computed twice except m^ on the sender: the
+// change d stays in registers across the first reduction and v across the second, and m^
+// is formed again from the stored levels when v is built, which keeps d, m^ and v from
+// being live all at once (that would cost a wave of occupancy per SIMD and with it the
+// chance to hold a whole launch on the chip at a time).
+template <int DT, int BITS, int MBITS, int ROUND, int TEAM, int CPL, bool SENDER>
 __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const char* act_s, char* out_s,
                                                   uint8_t* mcodes_s, float* mscales_s, uint8_t* codes_s,
                                                   float* scales_s, int64_t src0, int64_t g,
@@ -75,48 +106,46 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
     }
     __builtin_amdgcn_sched_barrier(0);
 
-    // ---- m^ = Q_z^-1(stored) ---------------------------------------------------------
-    const GroupScale msc = scale_from_wire<MBITS>(m_scale);
-    float v[CPL][kChunk];                                // holds m^, then v = m^ + Delta m
-#pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        float q[kChunk];
-        unpack_levels<MBITS>(mw[k], q);
-#pragma unroll
-        for (int e = 0; e < kChunk; ++e) v[k][e] = value_of(q[e], msc);
-    }
+    const GroupScale msc = scale_from_wire<MBITS>(m_scale);      // m^ = Q_z^-1(stored)
+    float v[CPL][kChunk];                                        // m^ + Delta m
+    float mx2 = 0.0f;                                            // max |v| for the storage scale
 
     if constexpr (SENDER) {
-        // ---- Delta m = Q_b(a - m^) ------------------------------------------------------
+        // ---- d = a - m^ and the wire scale ------------------------------------------------
         float d[CPL][kChunk];
         float mx = 0.0f;
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
-            float av[kChunk];
+            float m[kChunk], av[kChunk];
+            stored_values<MBITS>(mw[k], msc, m);
             unpack_raw<DT>(ra[k], av);
 #pragma unroll
             for (int e = 0; e < kChunk; ++e) {
-                d[k][e] = av[e] - v[k][e];
+                d[k][e] = av[e] - m[e];
                 mx = __builtin_fmaxf(mx, __builtin_fabsf(d[k][e]));
             }
         }
         mx = team_max_all<TEAM, 0>(mx, wave_max);
         const GroupScale sc = make_scale<BITS>(mx);
 #pragma unroll
+        for (int k = 0; k < CPL; ++k) forget(mw[k]);     // m^ is formed again below, not kept
+        // ---- Delta m = Q_b(d): codes out; v = m^ + Delta m ----------------------------------
+#pragma unroll
         for (int k = 0; k < CPL; ++k) {
             float r[kChunk];
-            if (a.stochastic) {
+            if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
                 chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
             } else {
 #pragma unroll
                 for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
             }
-            float q[kChunk];
+            float m[kChunk], q[kChunk];
+            stored_values<MBITS>(mw[k], msc, m);
 #pragma unroll
             for (int e = 0; e < kChunk; ++e) {
-                // the upper clamp of the stochastic form is a no-op for r = 1/2
-                q[e] = level_of<BITS, AQSGD_ROUND_STOCHASTIC>(d[k][e], sc, r[e]);
-                v[k][e] = v[k][e] + value_of(q[e], sc);
+                q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[e]);
+                v[k][e] = m[e] + value_of(q[e], sc);
+                mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
             }
             store_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS, pack_levels<BITS>(q));
         }
@@ -125,35 +154,41 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
         const GroupScale wsc = scale_from_wire<BITS>(wire_scale);
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
-            float q[kChunk];
+            float m[kChunk], q[kChunk];
+            stored_values<MBITS>(mw[k], msc, m);
             unpack_levels<BITS>(cw[k], q);
 #pragma unroll
-            for (int e = 0; e < kChunk; ++e) v[k][e] = v[k][e] + value_of(q[e], wsc);
+            for (int e = 0; e < kChunk; ++e) {
+                v[k][e] = m[e] + value_of(q[e], wsc);
+                mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
+            }
         }
     }
 
     // ---- store Q_z(v); the receiver also hands v on ------------------------------------
-    float mx2 = 0.0f;
-#pragma unroll
-    for (int k = 0; k < CPL; ++k)
-#pragma unroll
-        for (int e = 0; e < kChunk; ++e) mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
     mx2 = team_max_all<TEAM, 1>(mx2, wave_max);
     const GroupScale ssc = make_scale<MBITS>(mx2);
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        float q[kChunk];
+        float q2[kChunk];
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) q[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, kNearestOffset32);
-        store_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS, pack_levels<MBITS>(q));
+        for (int e = 0; e < kChunk; ++e) q2[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, kNearestOffset32);
+        store_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS, pack_levels<MBITS>(q2));
         if constexpr (!SENDER) store_raw_at<DT>(out_s + goff * kEB + cc[k] * kChunkBytes, pack_raw<DT>(v[k]));
     }
     if (lane_in_team == 0) mscales_s[g] = ssc.s_tx;
 }
 
-template <int DT, int BITS, int MBITS, int TEAM, int CPL, bool SENDER>
-__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
+// MODE: which side and, for the sender, how the message is rounded.
+enum LowbitMode { kLbReceiver = 0, kLbSenderNearest = 1, kLbSenderStochastic = 2 };
+
+// Four waves per SIMD hold a whole GPT2-sized launch (one wave per row) on the chip at
+// once; the hint makes the register allocator aim for that.
+template <int DT, int BITS, int MBITS, int TEAM, int CPL, int MODE>
+__global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock)) __attribute__((amdgpu_waves_per_eu(4)))
 void lowbit_team_kernel(const LowbitArgs a) {
+    constexpr bool SENDER = MODE != kLbReceiver;
+    constexpr int ROUND = MODE == kLbSenderStochastic ? AQSGD_ROUND_STOCHASTIC : AQSGD_ROUND_NEAREST;
     constexpr bool kMultiWave = TEAM > kWave;
     constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
@@ -183,9 +218,9 @@ void lowbit_team_kernel(const LowbitArgs a) {
              gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
             const int64_t g = gbase + team;
             if (g < a.gps)
-                lowbit_team_group<DT, BITS, MBITS, TEAM, CPL, SENDER>(a, act_s, out_s, mcodes_s, mscales_s,
-                                                                      codes_s, scales_s, src0, g, cc,
-                                                                      lane_in_team, wave_max);
+                lowbit_team_group<DT, BITS, MBITS, ROUND, TEAM, CPL, SENDER>(a, act_s, out_s, mcodes_s,
+                                                                             mscales_s, codes_s, scales_s, src0,
+                                                                             g, cc, lane_in_team, wave_max);
         }
     }
 }
@@ -203,32 +238,39 @@ template <int DT> hipError_t launch_lowbit_dt(int bits, int m_bits, int shape, b
                                               const LowbitArgs& a, hipStream_t stream);
 
 // ---- launch table (instantiated per dtype in aqsgd_lowbit_<dtype>.hip) ----------------
-template <int DT, int BITS, int MBITS, bool SENDER>
+template <int DT, int BITS, int MBITS, int MODE>
 static hipError_t launch_lb_shape(int shape, LaunchGeom g, const LowbitArgs& a, hipStream_t s) {
     const dim3 grid(g.grid_x, g.grid_y);
     switch (shape) {
-    case kLb8x1:    return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 8, 1, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb16x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 16, 1, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb32x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 32, 1, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb64x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 1, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb64x2:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb64x4:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, SENDER>, grid, dim3(kBlock), s, a);
-    case kLb256x2:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 2, SENDER>, grid, dim3(256), s, a);
-    case kLb256x4:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 4, SENDER>, grid, dim3(256), s, a);
-    case kLb1024x2: return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 1024, 2, SENDER>, grid, dim3(1024), s, a);
+    case kLb8x1:    return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 8, 1, MODE>, grid, dim3(kBlock), s, a);
+    case kLb16x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 16, 1, MODE>, grid, dim3(kBlock), s, a);
+    case kLb32x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 32, 1, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 1, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x2:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x4:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, MODE>, grid, dim3(kBlock), s, a);
+    case kLb256x2:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 2, MODE>, grid, dim3(256), s, a);
+    case kLb256x4:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 4, MODE>, grid, dim3(256), s, a);
+    case kLb1024x2: return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 1024, 2, MODE>, grid, dim3(1024), s, a);
     default:        return hipErrorInvalidValue;
+    }
+}
+
+template <int DT, int BITS, int MBITS>
+static hipError_t launch_lb_mode(int mode, int shape, LaunchGeom g, const LowbitArgs& a, hipStream_t s) {
+    switch (mode) {
+    case kLbReceiver:         return launch_lb_shape<DT, BITS, MBITS, kLbReceiver>(shape, g, a, s);
+    case kLbSenderNearest:    return launch_lb_shape<DT, BITS, MBITS, kLbSenderNearest>(shape, g, a, s);
+    case kLbSenderStochastic: return launch_lb_shape<DT, BITS, MBITS, kLbSenderStochastic>(shape, g, a, s);
+    default:                  return hipErrorInvalidValue;
     }
 }
 
 template <int DT, int BITS>
 static hipError_t launch_lb_mbits(int m_bits, int shape, bool sender, LaunchGeom g, const LowbitArgs& a,
                                   hipStream_t s) {
-    if (m_bits == 8)
-        return sender ? launch_lb_shape<DT, BITS, 8, true>(shape, g, a, s)
-                      : launch_lb_shape<DT, BITS, 8, false>(shape, g, a, s);
-    if (m_bits == 2)
-        return sender ? launch_lb_shape<DT, BITS, 2, true>(shape, g, a, s)
-                      : launch_lb_shape<DT, BITS, 2, false>(shape, g, a, s);
+    const int mode = !sender ? kLbReceiver : (a.stochastic ? kLbSenderStochastic : kLbSenderNearest);
+    if (m_bits == 8) return launch_lb_mode<DT, BITS, 8>(mode, shape, g, a, s);
+    if (m_bits == 2) return launch_lb_mode<DT, BITS, 2>(mode, shape, g, a, s);
     return hipErrorInvalidValue;
 }
 
