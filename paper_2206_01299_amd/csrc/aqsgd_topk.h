@@ -36,11 +36,16 @@ struct TopkArgs {
 constexpr int kTopkMaxGroup = 2048;
 constexpr int kTopkBits = 8;
 constexpr int kTopkBins = 256;
+constexpr int kTopkCopies = 4;                           // one histogram per row of 16 lanes
+constexpr int kTopkCopyWords = kTopkBins + kWave / kTopkCopies;   // 256 counters + one spare per lane of the row
 constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per lane for entries not kept
 
-// LDS of one wave.
+// LDS of one wave.  Magnitudes of one group crowd into a few values of the leading byte,
+// so lanes of one instruction often increment the same counter, which the LDS serialises;
+// each row of 16 lanes therefore counts into a histogram of its own and the four are added
+// when they are read.
 struct TopkLds {
-    uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
+    uint32_t bins[kTopkCopies * kTopkCopyWords];
     uint8_t stage[kTopkStageBytes];
 };
 
@@ -106,13 +111,17 @@ __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], co
 #pragma unroll
     for (int level = KeyBytes<DT>::value - 1; level >= 0; --level) {
         const int shift = 8 * level;
-        u32x4_t zero = {0u, 0u, 0u, 0u};
-        *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
+        const u32x4_t zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int c = 0; c < kTopkCopies; ++c)            // lane l clears counters 4l..4l+3 of every copy
+            *reinterpret_cast<u32x4_t*>(bins + c * kTopkCopyWords + 4 * lane) = zero;
+        uint32_t* mine_bins = bins + (lane / (kWave / kTopkCopies)) * kTopkCopyWords;
+        const uint32_t spare = static_cast<uint32_t>(kTopkBins + lane % (kWave / kTopkCopies));
         wave_lds_sync();
         // Below the top level only entries that share the decided bytes count.  With
         // those bytes cancelled by an exclusive-or, a sharing entry is left with its
         // byte (< 256) and every other entry with something larger, which min() sends
-        // to one of the lane's spare counters behind the 256 real ones (never read).
+        // to the lane's spare counter behind the 256 real ones of its row's copy (never read).
         const uint32_t decided = level == KeyBytes<DT>::value - 1 ? 0u : prefix << ((shift + 8) & 31);
 #pragma unroll
         for (int k = 0; k < CPL; ++k)
@@ -120,11 +129,13 @@ __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], co
 #pragma unroll
                 for (int e = 0; e < kChunk; ++e) {
                     const uint32_t digit = (u[k][e] ^ decided) >> shift;
-                    atomicAdd(&bins[min(digit, static_cast<uint32_t>(kTopkBins + lane))], 1u);
+                    atomicAdd(&mine_bins[min(digit, spare)], 1u);
                 }
             }
         wave_lds_sync();
-        const u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
+        u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
+#pragma unroll
+        for (int k = 1; k < kTopkCopies; ++k) c += *reinterpret_cast<const u32x4_t*>(bins + k * kTopkCopyWords + 4 * lane);
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
         uint32_t total;
         const uint32_t upto = wave_inclusive_sum(mine, lane, total);
@@ -188,7 +199,7 @@ __device__ __forceinline__ void lanes_before(const uint32_t (&cnt)[CPL], int lan
     }
 }
 
-template <int DT, int CPL>
+template <int DT, int CPL, int ROUND>
 __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
                                                  const bool (&valid)[CPL], int lane, TopkLds& lds) {
     constexpr int kEB = ElemBytes<DT>::value;
@@ -266,7 +277,7 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
     for (int k = 0; k < CPL; ++k) {
         uint32_t pos = row_start + kept_below[k];
         float r[kChunk];
-        if (a.stochastic) {
+        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
             chunk_uniforms(a.seed, static_cast<uint64_t>(e0) + static_cast<uint64_t>(cc[k]) * kChunk, r);
         } else {
 #pragma unroll
@@ -274,8 +285,7 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         }
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
-            // the upper clamp of the stochastic form is a no-op for r = 1/2
-            const float q = level_of<kTopkBits, AQSGD_ROUND_STOCHASTIC>(f[k][e], sc, r[e]);
+            const float q = level_of<kTopkBits, ROUND>(f[k][e], sc, r[e]);
             const uint32_t on = (keepb[k] >> e) & 1u;
             // entries that are not kept write this lane's spare byte
             lds.stage[on ? pos : static_cast<uint32_t>(kTopkMaxGroup + lane)] =
@@ -348,7 +358,8 @@ __device__ __forceinline__ void topk_dequant_group(const TopkArgs& a, int64_t g,
     wave_lds_sync();
 }
 
-template <int DT, int CPL, bool SENDER>
+// MODE: 0 receiver, 1 sender with nearest rounding, 2 sender with stochastic rounding.
+template <int DT, int CPL, int MODE>
 __global__ __launch_bounds__(kBlock)
 void topk_kernel(const TopkArgs a) {
     constexpr int kWaves = kBlock / kWave;
@@ -366,7 +377,8 @@ void topk_kernel(const TopkArgs a) {
     }
     for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave; g < a.n_groups;
          g += static_cast<int64_t>(gridDim.x) * kWaves) {
-        if constexpr (SENDER) topk_quant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+        if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
+        else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
         else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
     }
 }

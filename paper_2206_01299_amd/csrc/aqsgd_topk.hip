@@ -4,19 +4,20 @@
 
 namespace aqsgd {
 
-template <int DT, bool SENDER>
+template <int DT, int MODE>
 static hipError_t launch_topk_cpl(int cpl, unsigned blocks, const TopkArgs& a, hipStream_t s) {
     switch (cpl) {
-    case 1: return launch_kernel(topk_kernel<DT, 1, SENDER>, dim3(blocks), dim3(kBlock), s, a);
-    case 2: return launch_kernel(topk_kernel<DT, 2, SENDER>, dim3(blocks), dim3(kBlock), s, a);
-    case 4: return launch_kernel(topk_kernel<DT, 4, SENDER>, dim3(blocks), dim3(kBlock), s, a);
+    case 1: return launch_kernel(topk_kernel<DT, 1, MODE>, dim3(blocks), dim3(kBlock), s, a);
+    case 2: return launch_kernel(topk_kernel<DT, 2, MODE>, dim3(blocks), dim3(kBlock), s, a);
+    case 4: return launch_kernel(topk_kernel<DT, 4, MODE>, dim3(blocks), dim3(kBlock), s, a);
     default: return hipErrorInvalidValue;
     }
 }
 
 template <int DT>
 static hipError_t launch_topk_dt(int cpl, bool sender, unsigned blocks, const TopkArgs& a, hipStream_t s) {
-    return sender ? launch_topk_cpl<DT, true>(cpl, blocks, a, s) : launch_topk_cpl<DT, false>(cpl, blocks, a, s);
+    if (!sender) return launch_topk_cpl<DT, 0>(cpl, blocks, a, s);
+    return a.stochastic ? launch_topk_cpl<DT, 2>(cpl, blocks, a, s) : launch_topk_cpl<DT, 1>(cpl, blocks, a, s);
 }
 
 hipError_t launch_topk(int dtype, int cpl, bool sender, unsigned blocks, const TopkArgs& a, hipStream_t s) {
