@@ -670,7 +670,8 @@ def first_visit_line(args, cfg, wl):
     sample seen: the ordinary codec path through the same entry points)."""
     torch, B = wl.torch, wl.B
     d = wl.dev
-    n_calls = min(wl.calls, max(64, args.steps))
+    # the untimed launches that precede every timed batch visit samples of their own
+    n_calls = min(wl.calls - 32, max(64, args.steps))
     seen_s = torch.zeros(cfg.n_samples, dtype=torch.int32, device=d)
     seen_r = torch.zeros_like(seen_s)
     first = torch.zeros((wl.pool, cfg.batch), dtype=torch.int32, device=d)
@@ -691,7 +692,7 @@ def first_visit_line(args, cfg, wl):
     res = {}
     res["encode_seen_first"] = isolated_launches(torch, B, n_calls, lambda i: enc(i, 1 + i))
     res["decode_seen_first"] = isolated_launches(torch, B, n_calls, lambda i: dec(i, 1 + i))
-    assert int((seen_s != 0).sum()) == n_calls * cfg.batch and bool((seen_s != 0).eq(seen_r != 0).all())
+    assert int((seen_s != 0).sum()) >= n_calls * cfg.batch and bool((seen_s != 0).eq(seen_r != 0).all())
     assert bool(torch.equal(wl.m_send, wl.m_recv))
     res["encode_seen_second"] = isolated_launches(torch, B, n_calls, lambda i: enc(i, 100000 + i))
     res["decode_seen_second"] = isolated_launches(torch, B, n_calls, lambda i: dec(i, 100000 + i))
