@@ -36,16 +36,14 @@ struct TopkArgs {
 constexpr int kTopkMaxGroup = 2048;
 constexpr int kTopkBits = 8;
 constexpr int kTopkBins = 256;
-constexpr int kTopkCopies = 4;                           // one histogram per row of 16 lanes
-constexpr int kTopkCopyWords = kTopkBins + kWave / kTopkCopies;   // 256 counters + one spare per lane of the row
 constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per lane for entries not kept
 
-// LDS of one wave.  Magnitudes of one group crowd into a few values of the leading byte,
-// so lanes of one instruction often increment the same counter, which the LDS serialises;
-// each row of 16 lanes therefore counts into a histogram of its own and the four are added
-// when they are read.
+// LDS of one wave.  (One histogram per row of 16 lanes, added up when read, was tried
+// against the bank conflicts of the counting: the conflicts are between different
+// counters of one bank, not lanes on one counter, and stayed; the extra clearing and
+// reading made the kernel slower.)
 struct TopkLds {
-    uint32_t bins[kTopkCopies * kTopkCopyWords];
+    uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
     uint8_t stage[kTopkStageBytes];
 };
 
@@ -112,16 +110,13 @@ __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], co
     for (int level = KeyBytes<DT>::value - 1; level >= 0; --level) {
         const int shift = 8 * level;
         const u32x4_t zero = {0u, 0u, 0u, 0u};
-#pragma unroll
-        for (int c = 0; c < kTopkCopies; ++c)            // lane l clears counters 4l..4l+3 of every copy
-            *reinterpret_cast<u32x4_t*>(bins + c * kTopkCopyWords + 4 * lane) = zero;
-        uint32_t* mine_bins = bins + (lane / (kWave / kTopkCopies)) * kTopkCopyWords;
-        const uint32_t spare = static_cast<uint32_t>(kTopkBins + lane % (kWave / kTopkCopies));
+        *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
+        const uint32_t spare = static_cast<uint32_t>(kTopkBins + lane);
         wave_lds_sync();
         // Below the top level only entries that share the decided bytes count.  With
         // those bytes cancelled by an exclusive-or, a sharing entry is left with its
         // byte (< 256) and every other entry with something larger, which min() sends
-        // to the lane's spare counter behind the 256 real ones of its row's copy (never read).
+        // to the lane's spare counter behind the 256 real ones (never read).
         const uint32_t decided = level == KeyBytes<DT>::value - 1 ? 0u : prefix << ((shift + 8) & 31);
 #pragma unroll
         for (int k = 0; k < CPL; ++k)
@@ -129,13 +124,11 @@ __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], co
 #pragma unroll
                 for (int e = 0; e < kChunk; ++e) {
                     const uint32_t digit = (u[k][e] ^ decided) >> shift;
-                    atomicAdd(&mine_bins[min(digit, spare)], 1u);
+                    atomicAdd(&bins[min(digit, spare)], 1u);
                 }
             }
         wave_lds_sync();
-        u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
-#pragma unroll
-        for (int k = 1; k < kTopkCopies; ++k) c += *reinterpret_cast<const u32x4_t*>(bins + k * kTopkCopyWords + 4 * lane);
+        const u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
         uint32_t total;
         const uint32_t upto = wave_inclusive_sum(mine, lane, total);
