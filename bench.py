@@ -23,17 +23,31 @@ between two HIP events on the launching stream, with device synchronisation on b
 sides; event time / K is ms_per_step.  `value` is the metric's own quantity: the
 activation bytes of a micro-batch over the time of its encode + decode, from a second
 timed run of the same K micro-batches without the backward message.
-Micro-batches touch disjoint samples and pool slots, so their codec calls are
-independent, as they are in a pipeline stage that has several micro-batches in
-flight: with --streams N (default 4) the forward pairs (encode then decode) are
-dealt round-robin over N/2 streams and the backward pairs over the other N/2, and
-a kernel's launch and completion latency overlaps other kernels' streaming.
---streams 1 runs the four kernels of every step strictly one after the other.
+How the messages are launched (--schedule):
+  pipeline  (default) one aqsgd_run_jobs launch per time slot of the two stages, as when
+            the sending and the receiving stage work on neighbouring micro-batches at the
+            same time: encode of micro-batch k, decode and grad_quant of k-1, grad_dequant
+            of k-2, all independent, 124.6 MB in one grid.  Every message of every timed
+            micro-batch is launched exactly once (the first and last slots of a chain carry
+            fewer jobs).
+  stage     one launch per stage and micro-batch: the sending stage's encode(k) +
+            grad_dequant(k-1), the receiving stage's decode(k) + grad_quant(k).
+  calls     the four single-message calls.
+Micro-batches touch disjoint samples and pool slots, so their chains are independent, as
+they are in a pipeline that has several micro-batches in flight: they are dealt
+round-robin over --streams streams (default 2; 4 for `calls`, half of them for the forward
+and half for the backward messages), and one launch's fill and drain overlaps another's
+streaming.  --streams 1 runs every launch strictly after the one before.
 
-A further pass over the same K steps launches every kernel on its own, one after
-the other, through the library's timed-launch hook, which stamps a HIP event pair
-with the kernel's own begin and end on its stream; those per-launch durations feed
-the roofline figure (kernel quality), independent of how launches are overlapped.
+A further pass launches every kind of launch on its own, one after the other, through
+the library's timed-launch hook, which stamps a HIP event pair with the kernel's own
+begin and end on its stream: the four single-message calls and the schedule's fused
+launch.  The longest launch of the schedule feeds the roofline figure (kernel quality),
+independent of how launches are overlapped.
+
+Secondary lines: --first-visit (Algorithm 1's uncompressed first visits against a same-run
+copy), --ceilings (what launches of this size reach on this GPU), --config, --m-bits,
+--bwd-keep.
 
 Prints ONE JSON line.
 """
@@ -76,11 +90,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--streams", type=int, choices=[1, 2, 4, 8], default=2,
-                    help="1: the four kernels of a step run one after the other on one stream; "
-                         "N>1: N/2 streams carry forward pairs (encode then decode of one micro-batch) "
-                         "and N/2 carry backward pairs, micro-batches dealt round-robin; micro-batches "
-                         "touch disjoint samples and pool slots, so the chains are independent")
+    ap.add_argument("--streams", type=int, choices=[0, 1, 2, 4, 8], default=0,
+                    help="streams the micro-batches are dealt over (they touch disjoint samples and pool "
+                         "slots, so their chains are independent); 0 = 2 for the fused schedules, 4 for "
+                         "`calls` (where half of the streams carry forward pairs and half backward pairs); "
+                         "1: every launch strictly after the one before")
     ap.add_argument("--schedule", choices=["calls", "stage", "pipeline"], default="pipeline",
                     help="calls: four single-message calls per step; stage / pipeline: the same messages "
                          "through aqsgd_run_jobs, two launches (one per stage) or one launch (one time "
@@ -388,10 +402,14 @@ class DeviceClock:
         return a.elapsed_time(b) * 1e-3, wall
 
 
-def evict_caches(torch, scratch):
-    """Overwrite 1 GiB, four times the last-level cache, so that the next kernels find
-    none of their rows cached."""
-    scratch.add_(1)
+def evict_caches(torch, scratch, footprint_bytes):
+    """Make sure the next kernels find none of their rows cached.  A region that itself
+    touches more than 1 GiB of distinct rows (four times the last-level cache) has evicted
+    its own first rows by the time its untimed replay ends; a smaller one is followed by a
+    pass over 1 GiB of scratch.  (That pass leaves the cache full of modified lines, whose
+    write-back would be charged to the timed kernels: it is not made where it is not needed.)"""
+    if footprint_bytes < (1 << 30):
+        scratch.add_(1)
     torch.cuda.synchronize()
 
 
@@ -453,7 +471,8 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True, schedule="ca
     with torch.cuda.stream(main):
         for g in graphs:                                 # untimed: uploads the graphs
             g.replay()
-    evict_caches(torch, wl.evict)
+    lb = wl.leg_bytes()
+    evict_caches(torch, wl.evict, count * sum(lb[l] for l in (wl.LEGS if backward else wl.LEGS[:2])))
 
     def replay_all():
         for g in graphs:
@@ -491,7 +510,8 @@ def one_stream_forward_pairs(wl, first, count=256, warm=20):
             wl.step(k, backward=False)
     with torch.cuda.stream(main):
         g.replay()
-    evict_caches(torch, wl.evict)
+    lb = wl.leg_bytes()
+    evict_caches(torch, wl.evict, count * (lb["encode"] + lb["decode"]))
     dev, _ = DeviceClock(torch, main).time(g.replay)
     return dev / count
 
@@ -613,8 +633,8 @@ def cpu_baseline(cfg, calls):
 
 
 def read_traffic():
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3
-    counter summary (None if it has not been collected)."""
+    """HBM bytes per launch from the committed rocprofv3 counter summary (a stored value,
+    labelled as such in the line; None if it has not been collected)."""
     f = ROOT / "profiles" / "hbm_traffic_gpt2_fw4.txt"
     if not f.exists():
         return None
@@ -867,6 +887,8 @@ def main():
     sched = args.schedule
     if args.m_bits or args.bwd_keep:
         sched = "calls"                                  # these variants have single-message calls only
+    if args.streams == 0:
+        args.streams = 4 if sched == "calls" else 2
     step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams, schedule=sched)
     fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False, schedule=sched)
     ms_per_step = step_dev / K * 1e3
@@ -891,7 +913,7 @@ def main():
                     "algorithmic_bytes_per_launch": lb[dominant],
                     "avg_launch_us": round(legs[dominant]["avg_us"], 3),
                     "launches_timed": legs[dominant]["launches"],
-                    "traffic": (traffic or {}).get(f"{dominant}_hbm_bytes_per_launch"),
+                    "traffic": (traffic or {}).get(f"{dominant.split('(')[0]}_hbm_bytes_per_launch"),
                     "traffic_source": "stored rocprofv3 counter value (profiles/hbm_traffic_gpt2_fw4.txt), "
                                       "not measured in this run" if traffic else None}
         pair_us = legs["encode"]["avg_us"] + legs["decode"]["avg_us"]
