@@ -45,6 +45,7 @@ constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per
 struct TopkLds {
     uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
     uint8_t stage[kTopkStageBytes];
+    uint16_t stage16[kTopkMaxGroup + kWave];             // kept entries as stored, + one spare per lane
 };
 
 // Bytes of a magnitude key: the key is the magnitude's bit pattern shifted left by
@@ -192,6 +193,227 @@ __device__ __forceinline__ void lanes_before(const uint32_t (&cnt)[CPL], int lan
     }
 }
 
+// ---------------------------------------------------------------------------
+// Sixteen-bit types with nearest rounding: the sender works on the magnitudes as they
+// sit in memory, two per register (packed 16-bit integer operations), and quantises
+// only the entries that are kept.  The kernel is bound by vector arithmetic (a wave64
+// instruction occupies its SIMD for four cycles, and a group is a thousand of them in
+// the general path below), so instructions are what this path saves: no conversion of
+// all entries to binary32, no unpacked keys, digits of the radix select cut straight
+// out of the packed words, masks from the sign bits of packed differences, and one
+// quantisation per kept entry instead of one per entry.
+// ---------------------------------------------------------------------------
+typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
+
+__device__ __forceinline__ uint32_t pk_max_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(u16x2_t, a),
+                                                                  __builtin_bit_cast(u16x2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, a),
+                                                                  __builtin_bit_cast(u16x2_t, b)));
+}
+__device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) - __builtin_bit_cast(u16x2_t, b));
+}
+
+// binary32 value of a 16-bit storage pattern.
+template <int DT>
+__device__ __forceinline__ float f32_of_bits16(uint32_t h) {
+    if constexpr (DT == AQSGD_F16) return static_cast<float>(__builtin_bit_cast(_Float16, static_cast<uint16_t>(h)));
+    else return bf16_bits_to_f32(h);
+}
+
+// One level of the radix select for packed 15-bit magnitudes.  LEVEL 1 counts the top
+// eight bits of every entry; LEVEL 0 counts the low seven bits of the entries whose top
+// eight bits are `prefix` (with those bits cancelled by an exclusive-or a sharing entry
+// is left below 128 and every other entry at 128 or above: min() sends the large ones to
+// the lane's spare counter, and counters 128..255 are left out of the search).  Returns the digit that holds rank `need` and updates need / in_bin.
+template <int CPL, int LEVEL>
+__device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], const bool (&valid)[CPL],
+                                                  uint32_t prefix, int lane, uint32_t* bins, uint32_t& need,
+                                                  uint32_t& in_bin) {
+    const u32x4_t zero = {0u, 0u, 0u, 0u};
+    *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
+    wave_lds_sync();
+    const uint32_t spare = static_cast<uint32_t>(kTopkBins + lane);
+    const uint32_t cancel = (prefix << 7) | (prefix << 23);
+    const uint32_t spare2 = spare | (spare << 16);
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+        if (valid[k]) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                if constexpr (LEVEL == 1) {
+                    atomicAdd(&bins[(m[k][i] >> 7) & 0xffu], 1u);
+                    atomicAdd(&bins[m[k][i] >> 23], 1u);
+                } else {
+                    const uint32_t y = pk_min_u16(m[k][i] ^ cancel, spare2);
+                    atomicAdd(&bins[y & 0xffffu], 1u);
+                    atomicAdd(&bins[y >> 16], 1u);
+                }
+            }
+        }
+    wave_lds_sync();
+    u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
+    // At the low level a sharing entry counts below 128; an entry whose leading bits differ
+    // only a little lands in counters 128..255, which therefore do not count.
+    if (LEVEL == 0 && lane >= kWave / 2) c = zero;
+    const uint32_t mine = c[0] + c[1] + c[2] + c[3];
+    uint32_t total;
+    const uint32_t upto = wave_inclusive_sum(mine, lane, total);
+    // entries in counters above this lane's four, then above each of its counters
+    const uint32_t a3 = total - upto;
+    const uint32_t a2 = a3 + c[3], a1 = a2 + c[2], a0 = a1 + c[1];
+    const bool here = a3 < need && need <= a3 + mine;                // exactly one lane
+    const int sel = need <= a2 ? 3 : (need <= a1 ? 2 : (need <= a0 ? 1 : 0));
+    const uint32_t above = sel == 3 ? a3 : (sel == 2 ? a2 : (sel == 1 ? a1 : a0));
+    const uint32_t count = sel == 3 ? c[3] : (sel == 2 ? c[2] : (sel == 1 ? c[1] : c[0]));
+    const uint64_t who = __ballot(here);
+    const int src = who ? __builtin_ctzll(who) : 0;
+    const uint32_t digit = __builtin_amdgcn_readlane(static_cast<uint32_t>(4 * lane + sel), src);
+    need -= __builtin_amdgcn_readlane(above, src);
+    in_bin = __builtin_amdgcn_readlane(count, src);
+    return digit;
+}
+
+// Bit e of the result: entry e of the chunk has its sign bit set in the packed
+// differences d[0..3] (entry 2i in the low half of d[i], entry 2i+1 in the high half).
+__device__ __forceinline__ uint32_t sign_mask16(const uint32_t (&d)[4]) {
+    uint32_t mask = 0;
+#pragma unroll
+    for (int i = 3; i >= 0; --i) {                       // last entry first: (mask << 1) | sign
+        mask = __builtin_amdgcn_alignbit(mask, d[i], 31);
+        mask = __builtin_amdgcn_alignbit(mask, d[i] << 16, 31);
+    }
+    return mask;
+}
+
+template <int DT, int CPL>
+__device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
+                                                   const bool (&valid)[CPL], int lane, TopkLds& lds) {
+    constexpr int kChunkBytes = kChunk * 2;
+    const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
+    const char* src = static_cast<const char*>(a.grad) + e0 * 2;
+
+    Raw<DT> raw[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) raw[k] = load_raw_at<DT>(src + cc[k] * kChunkBytes);
+    __builtin_amdgcn_sched_barrier(0);
+
+    // ---- magnitudes (two per register) and the group's largest ------------------------------
+    uint32_t m[CPL][4];
+    uint32_t top = 0;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {                    // a clamped lane repeats a real chunk: harmless here
+            m[k][i] = raw[k].v[i] & 0x7fff7fffu;
+            top = pk_max_u16(top, m[k][i]);
+        }
+    top = max(top & 0xffffu, top >> 16);
+    top = __float_as_uint(team_max<kWave>(__uint_as_float(top)));    // an integer maximum over the lanes
+    const GroupScale sc = make_scale<kTopkBits>(f32_of_bits16<DT>(top));
+
+    // ---- the keep-th largest magnitude: two levels, eight then seven bits ---------------------
+    uint32_t need = static_cast<uint32_t>(a.keep), in_bin = 0;
+    const uint32_t hi8 = radix_level16<CPL, 1>(m, valid, 0u, lane, lds.bins, need, in_bin);
+    const uint32_t lo7 = radix_level16<CPL, 0>(m, valid, hi8, lane, lds.bins, need, in_bin);
+    const uint32_t threshold = (hi8 << 7) | lo7;
+    const int equal_kept = static_cast<int>(need), equal_total = static_cast<int>(in_bin);
+    const uint32_t tt = threshold | (threshold << 16);
+
+    // ---- keep flags: everything above the threshold, and the first equal_kept entries equal to it
+    uint32_t geb[CPL];                                   // bit e: entry e is >= the threshold
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        uint32_t d[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(m[k][i], tt);      // sign set: below the threshold
+        geb[k] = valid[k] ? ~sign_mask16(d) & 0xffu : 0u;
+    }
+    uint32_t keepb[CPL];
+    if (equal_kept == equal_total) {                     // no choice to make among equals (wave-uniform)
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) keepb[k] = geb[k];
+    } else {
+        uint32_t gtb[CPL], eqb[CPL], ties[CPL], ties_below[CPL], ties_total[CPL];
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            uint32_t d[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(tt, m[k][i]);  // sign set: above the threshold
+            gtb[k] = sign_mask16(d) & geb[k];
+            eqb[k] = geb[k] & ~gtb[k];
+            ties[k] = __builtin_popcount(eqb[k]);
+        }
+        lanes_before<CPL>(ties, lane, ties_below, ties_total);
+        int left = equal_kept;                           // equals still to keep when chunk row k starts
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            const int allowed = left - static_cast<int>(ties_below[k]);   // ... when this lane's chunk starts
+            // all of the chunk's equals, or none of them, unless the cut falls inside the chunk
+            uint32_t kb = gtb[k] | (static_cast<int>(ties[k]) <= allowed ? eqb[k] : 0u);
+            if (allowed > 0 && allowed < static_cast<int>(ties[k])) {    // rare: at most one lane per row
+                int seen = 0;
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e) {
+                    const uint32_t eq = (eqb[k] >> e) & 1u;
+                    if (eq && seen < allowed) kb |= 1u << e;
+                    seen += static_cast<int>(eq);
+                }
+            }
+            keepb[k] = kb;
+            left = max(left - static_cast<int>(ties_total[k]), 0);
+        }
+    }
+
+    // ---- the kept entries, as stored, in entry order into LDS ----------------------------------
+    uint32_t kept[CPL], kept_below[CPL], kept_total[CPL];
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) kept[k] = __builtin_popcount(keepb[k]);
+    lanes_before<CPL>(kept, lane, kept_below, kept_total);
+    const uint32_t spare = static_cast<uint32_t>(kTopkMaxGroup + lane);   // entries not kept land here
+    uint32_t row_start = 0;
+#pragma unroll
+    for (int k = 0; k < CPL; ++k) {
+        uint32_t pos = row_start + kept_below[k];
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) {
+            const uint32_t on = (keepb[k] >> e) & 1u;
+            const uint32_t w = raw[k].v[e / 2];
+            lds.stage16[on ? pos : spare] = static_cast<uint16_t>(e % 2 ? w >> 16 : w);
+            pos += on;
+        }
+        if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb[k]);
+        row_start += kept_total[k];
+    }
+    wave_lds_sync();
+
+    // ---- quantise the kept entries: lane l takes a run of consecutive positions ---------------
+    const int run = (a.keep + kWave - 1) / kWave;
+    for (int j = 0; j < run; ++j) {
+        const int p = lane * run + j;
+        if (p < a.keep) {
+            const float f = f32_of_bits16<DT>(lds.stage16[p]);
+            const float q = level_of<kTopkBits, AQSGD_ROUND_NEAREST>(f, sc, kNearestOffset32);
+            lds.stage[p] = static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_u8_f32(q, 0, 0));
+        }
+    }
+    wave_lds_sync();
+
+    // ---- the group's bytes leave LDS ------------------------------------------------------
+    uint8_t* dst = a.codes + g * a.keep;
+    if (a.keep % 16 == 0) {
+        for (int i = lane; i < a.keep / 16; i += kWave)
+            *reinterpret_cast<u32x4_t*>(dst + 16 * i) = *reinterpret_cast<const u32x4_t*>(lds.stage + 16 * i);
+    } else {
+        for (int i = lane; i < a.keep; i += kWave) dst[i] = lds.stage[i];
+    }
+    if (lane == 0) a.scales[g] = sc.s_tx;
+    wave_lds_sync();                                     // the next group reuses the staging bytes
+}
+
 template <int DT, int CPL, int ROUND>
 __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
                                                  const bool (&valid)[CPL], int lane, TopkLds& lds) {
@@ -247,13 +469,16 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
             const int allowed = left - static_cast<int>(ties_below[k]);   // ... when this lane's chunk starts
-            uint32_t kb = gtb[k];
-            int seen = 0;
+            // all of the chunk's equals, or none of them, unless the cut falls inside the chunk
+            uint32_t kb = gtb[k] | (static_cast<int>(ties[k]) <= allowed ? eqb[k] : 0u);
+            if (allowed > 0 && allowed < static_cast<int>(ties[k])) {    // rare: at most one lane per row
+                int seen = 0;
 #pragma unroll
-            for (int e = 0; e < kChunk; ++e) {
-                const uint32_t eq = (eqb[k] >> e) & 1u;
-                if (eq && seen < allowed) kb |= 1u << e;
-                seen += static_cast<int>(eq);
+                for (int e = 0; e < kChunk; ++e) {
+                    const uint32_t eq = (eqb[k] >> e) & 1u;
+                    if (eq && seen < allowed) kb |= 1u << e;
+                    seen += static_cast<int>(eq);
+                }
             }
             keepb[k] = kb;
             left = max(left - static_cast<int>(ties_total[k]), 0);
@@ -370,7 +595,8 @@ void topk_kernel(const TopkArgs a) {
     }
     for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave; g < a.n_groups;
          g += static_cast<int64_t>(gridDim.x) * kWaves) {
-        if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
+        if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) topk_quant_group16<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+        else if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
         else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
         else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
     }
