@@ -453,7 +453,7 @@ int run_topk(const aqsgd_desc* d, int32_t keep, bool sender, const void* grad, v
     a.group = d->group; a.cpg = d->group / kChunk; a.keep = keep;
     a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
     const int cpl = a.cpg <= kWave ? 1 : (a.cpg <= 2 * kWave ? 2 : 4);
-    const LaunchGeom g = geometry(a.n_groups, kBlock / kWave, 1,
+    const LaunchGeom g = geometry(a.n_groups, kTopkBlock / kWave, 1,
                                   max_blocks_knob().load(std::memory_order_relaxed));
     const hipError_t err = launch_topk(d->dtype, cpl, sender, g.grid_x, a, stream);
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;

@@ -42,6 +42,11 @@ constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per
 // against the bank conflicts of the counting: the conflicts are between different
 // counters of one bank, not lanes on one counter, and stayed; the extra clearing and
 // reading made the kernel slower.)
+// One wave per workgroup: a group is a wave's work and the waves share nothing, and with a
+// single TopkLds per workgroup every LDS address is an instruction offset instead of a
+// register sum (one vector instruction less per histogram update and per staged entry).
+constexpr int kTopkBlock = kWave;
+
 struct TopkLds {
     uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
     uint8_t stage[kTopkStageBytes];
@@ -373,17 +378,23 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
 #pragma unroll
     for (int k = 0; k < CPL; ++k) kept[k] = __builtin_popcount(keepb[k]);
     lanes_before<CPL>(kept, lane, kept_below, kept_total);
-    const uint32_t spare = static_cast<uint32_t>(kTopkMaxGroup + lane);   // entries not kept land here
+    // An entry that is not kept lands in the lane's spare slot behind the staged ones.  Byte
+    // offsets, and the choice written as spare + on * (position - spare): three vector
+    // instructions per entry (extract, multiply-add, advance) where compare + select took five.
+    char* const stage16 = reinterpret_cast<char*>(lds.stage16);
+    const int spare = 2 * (kTopkMaxGroup + lane);
     uint32_t row_start = 0;
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        uint32_t pos = row_start + kept_below[k];
+        int ahead = 2 * static_cast<int>(row_start + kept_below[k]) - spare;     // negative: the spares come last
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) {
-            const uint32_t on = (keepb[k] >> e) & 1u;
+            const int on = static_cast<int>((keepb[k] >> e) & 1u);
             const uint32_t w = raw[k].v[e / 2];
-            lds.stage16[on ? pos : spare] = static_cast<uint16_t>(e % 2 ? w >> 16 : w);
-            pos += on;
+            *reinterpret_cast<uint16_t*>(stage16 + (__mul24(on, ahead) + spare)) =
+                static_cast<uint16_t>(e % 2 ? w >> 16 : w);
+            ahead += 2 * on;
+            asm volatile("" : "+v"(ahead));              // keeps the running difference in its register
         }
         if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb[k]);
         row_start += kept_total[k];
@@ -578,13 +589,13 @@ __device__ __forceinline__ void topk_dequant_group(const TopkArgs& a, int64_t g,
 
 // MODE: 0 receiver, 1 sender with nearest rounding, 2 sender with stochastic rounding.
 template <int DT, int CPL, int MODE>
-__global__ __launch_bounds__(kBlock)
+__global__ __launch_bounds__(kTopkBlock)
 void topk_kernel(const TopkArgs a) {
-    constexpr int kWaves = kBlock / kWave;
+    constexpr int kWaves = kTopkBlock / kWave;
     __shared__ __align__(16) TopkLds lds_all[kWaves];
 
     const int lane = threadIdx.x % kWave;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
     uint32_t cc[CPL];
     bool valid[CPL];
 #pragma unroll
