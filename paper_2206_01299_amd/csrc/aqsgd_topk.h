@@ -218,6 +218,9 @@ __device__ __forceinline__ uint32_t pk_min_u16(uint32_t a, uint32_t b) {
     return __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(u16x2_t, a),
                                                                   __builtin_bit_cast(u16x2_t, b)));
 }
+__device__ __forceinline__ uint32_t pk_add_u16(uint32_t a, uint32_t b) {
+    return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) + __builtin_bit_cast(u16x2_t, b));
+}
 __device__ __forceinline__ uint32_t pk_sub_u16(uint32_t a, uint32_t b) {
     return __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, a) - __builtin_bit_cast(u16x2_t, b));
 }
@@ -229,11 +232,14 @@ __device__ __forceinline__ float f32_of_bits16(uint32_t h) {
     else return bf16_bits_to_f32(h);
 }
 
-// One level of the radix select for packed 15-bit magnitudes.  LEVEL 1 counts the top
-// eight bits of every entry; LEVEL 0 counts the low seven bits of the entries whose top
-// eight bits are `prefix` (with those bits cancelled by an exclusive-or a sharing entry
-// is left below 128 and every other entry at 128 or above: min() sends the large ones to
-// the lane's spare counter, and counters 128..255 are left out of the search).  Returns the digit that holds rank `need` and updates need / in_bin.
+// One level of the radix select for packed magnitudes held doubled (m2 = 2 * magnitude:
+// adding a stored pattern to itself drops the sign bit, and it leaves the magnitude's top
+// eight bits in a byte of their own, which a counter's address is one instruction away
+// from).  LEVEL 1 counts that byte for every entry; LEVEL 0 counts the other byte (twice
+// the low seven bits: even counters only) for the entries whose top byte is `prefix`: with
+// that byte cancelled by an exclusive-or a sharing entry is left below 256 and every other
+// entry at 256 or above, where min() caps it at the lane's spare counter (counters from
+// 256 on are never read).  Returns the digit that holds rank `need` and updates need / in_bin.
 template <int CPL, int LEVEL>
 __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], const bool (&valid)[CPL],
                                                   uint32_t prefix, int lane, uint32_t* bins, uint32_t& need,
@@ -242,7 +248,7 @@ __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], c
     *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
     wave_lds_sync();
     const uint32_t spare = static_cast<uint32_t>(kTopkBins + lane);
-    const uint32_t cancel = (prefix << 7) | (prefix << 23);
+    const uint32_t cancel = (prefix << 8) | (prefix << 24);
     const uint32_t spare2 = spare | (spare << 16);
 #pragma unroll
     for (int k = 0; k < CPL; ++k)
@@ -250,8 +256,8 @@ __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], c
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 if constexpr (LEVEL == 1) {
-                    atomicAdd(&bins[(m[k][i] >> 7) & 0xffu], 1u);
-                    atomicAdd(&bins[m[k][i] >> 23], 1u);
+                    atomicAdd(&bins[(m[k][i] >> 8) & 0xffu], 1u);
+                    atomicAdd(&bins[m[k][i] >> 24], 1u);
                 } else {
                     const uint32_t y = pk_min_u16(m[k][i] ^ cancel, spare2);
                     atomicAdd(&bins[y & 0xffffu], 1u);
@@ -261,9 +267,6 @@ __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], c
         }
     wave_lds_sync();
     u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
-    // At the low level a sharing entry counts below 128; an entry whose leading bits differ
-    // only a little lands in counters 128..255, which therefore do not count.
-    if (LEVEL == 0 && lane >= kWave / 2) c = zero;
     const uint32_t mine = c[0] + c[1] + c[2] + c[3];
     uint32_t total;
     const uint32_t upto = wave_inclusive_sum(mine, lane, total);
@@ -294,37 +297,40 @@ __device__ __forceinline__ uint32_t sign_mask16(const uint32_t (&d)[4]) {
     return mask;
 }
 
+// The group's entries as stored, one chunk per lane and row.
 template <int DT, int CPL>
-__device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
-                                                   const bool (&valid)[CPL], int lane, TopkLds& lds) {
-    constexpr int kChunkBytes = kChunk * 2;
-    const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
-    const char* src = static_cast<const char*>(a.grad) + e0 * 2;
-
-    Raw<DT> raw[CPL];
+__device__ __forceinline__ void load_group16(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
+                                             Raw<DT> (&raw)[CPL]) {
+    const char* src = static_cast<const char*>(a.grad) + g * a.group * 2;
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) raw[k] = load_raw_at<DT>(src + cc[k] * kChunkBytes);
-    __builtin_amdgcn_sched_barrier(0);
+    for (int k = 0; k < CPL; ++k) raw[k] = load_raw_at<DT>(src + cc[k] * (kChunk * 2));
+}
 
-    // ---- magnitudes (two per register) and the group's largest ------------------------------
-    uint32_t m[CPL][4];
+template <int DT, int CPL>
+__device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g, const Raw<DT> (&raw)[CPL],
+                                                   const uint32_t (&cc)[CPL], const bool (&valid)[CPL], int lane,
+                                                   TopkLds& lds) {
+    const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
+
+    // ---- doubled magnitudes (two per register) and the group's largest ------------------------
+    uint32_t m2[CPL][4];
     uint32_t top = 0;
 #pragma unroll
     for (int k = 0; k < CPL; ++k)
 #pragma unroll
         for (int i = 0; i < 4; ++i) {                    // a clamped lane repeats a real chunk: harmless here
-            m[k][i] = raw[k].v[i] & 0x7fff7fffu;
-            top = pk_max_u16(top, m[k][i]);
+            m2[k][i] = pk_add_u16(raw[k].v[i], raw[k].v[i]);
+            top = pk_max_u16(top, m2[k][i]);
         }
-    top = max(top & 0xffffu, top >> 16);
+    top = max(top & 0xffffu, top >> 16) >> 1;
     top = __float_as_uint(team_max<kWave>(__uint_as_float(top)));    // an integer maximum over the lanes
     const GroupScale sc = make_scale<kTopkBits>(f32_of_bits16<DT>(top));
 
     // ---- the keep-th largest magnitude: two levels, eight then seven bits ---------------------
     uint32_t need = static_cast<uint32_t>(a.keep), in_bin = 0;
-    const uint32_t hi8 = radix_level16<CPL, 1>(m, valid, 0u, lane, lds.bins, need, in_bin);
-    const uint32_t lo7 = radix_level16<CPL, 0>(m, valid, hi8, lane, lds.bins, need, in_bin);
-    const uint32_t threshold = (hi8 << 7) | lo7;
+    const uint32_t hi8 = radix_level16<CPL, 1>(m2, valid, 0u, lane, lds.bins, need, in_bin);
+    const uint32_t lo7x2 = radix_level16<CPL, 0>(m2, valid, hi8, lane, lds.bins, need, in_bin);
+    const uint32_t threshold = ((hi8 << 8) | lo7x2) >> 1;
     const int equal_kept = static_cast<int>(need), equal_total = static_cast<int>(in_bin);
     const uint32_t tt = threshold | (threshold << 16);
 
@@ -334,7 +340,7 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
     for (int k = 0; k < CPL; ++k) {
         uint32_t d[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(m[k][i], tt);      // sign set: below the threshold
+        for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(raw[k].v[i] & 0x7fff7fffu, tt);   // sign set: below the threshold
         geb[k] = valid[k] ? ~sign_mask16(d) & 0xffu : 0u;
     }
     uint32_t keepb[CPL];
@@ -347,7 +353,7 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
         for (int k = 0; k < CPL; ++k) {
             uint32_t d[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(tt, m[k][i]);  // sign set: above the threshold
+            for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(tt, raw[k].v[i] & 0x7fff7fffu);   // sign set: above the threshold
             gtb[k] = sign_mask16(d) & geb[k];
             eqb[k] = geb[k] & ~gtb[k];
             ties[k] = __builtin_popcount(eqb[k]);
@@ -604,9 +610,26 @@ void topk_kernel(const TopkArgs a) {
         valid[k] = c < a.cpg;
         cc[k] = static_cast<uint32_t>(min(c, a.cpg - 1));
     }
+    if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) {
+        // The loads of the wave's first group go out before anything else: a launch is one
+        // round of waves that all start by waiting for memory, and whatever does not depend
+        // on the data (lane constants, clearing counters) is then worked off during that wait.
+        int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+        if (g >= a.n_groups) return;
+        Raw<DT> raw[CPL];
+        load_group16<DT, CPL>(a, g, cc, raw);
+        __builtin_amdgcn_sched_barrier(0);
+        for (;;) {
+            topk_quant_group16<DT, CPL>(a, g, raw, cc, valid, lane, lds_all[wave]);
+            g += static_cast<int64_t>(gridDim.x) * kWaves;
+            if (g >= a.n_groups) break;
+            load_group16<DT, CPL>(a, g, cc, raw);
+        }
+        return;
+    }
     for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave; g < a.n_groups;
          g += static_cast<int64_t>(gridDim.x) * kWaves) {
-        if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) topk_quant_group16<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+        if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) { }
         else if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
         else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
         else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
