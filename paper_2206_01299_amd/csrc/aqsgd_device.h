@@ -153,6 +153,34 @@ __device__ __forceinline__ float f32_plus_f16hi(float x, uint32_t m) {
     return d;
 }
 
+__device__ __forceinline__ float f16lo_minus_f32(uint32_t a, float m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(m));
+    return d;
+}
+__device__ __forceinline__ float f16hi_minus_f32(uint32_t a, float m) {
+    float d;
+    asm("v_fma_mix_f32 %0, %1, 1.0, -%2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(d) : "v"(a), "v"(m));
+    return d;
+}
+
+// d[e] = binary32(a[e]) - m[e] for one chunk, m already in binary32.
+template <int DT>
+__device__ __forceinline__ void delta_from_values(const Raw<DT>& a, const float (&m)[kChunk], float (&d)[kChunk]) {
+    if constexpr (DT == AQSGD_F16) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            d[2 * e] = f16lo_minus_f32(a.v[e], m[2 * e]);
+            d[2 * e + 1] = f16hi_minus_f32(a.v[e], m[2 * e + 1]);
+        }
+    } else {
+        float av[kChunk];
+        unpack_raw<DT>(a, av);
+#pragma unroll
+        for (int e = 0; e < kChunk; ++e) d[e] = av[e] - m[e];
+    }
+}
+
 // d[e] = binary32(a[e]) - binary32(m[e]) for one chunk.
 template <int DT>
 __device__ __forceinline__ void delta_chunk(const Raw<DT>& a, const Raw<DT>& m, float (&d)[kChunk]) {

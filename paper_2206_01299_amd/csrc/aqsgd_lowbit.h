@@ -110,7 +110,43 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
     float v[CPL][kChunk];                                        // m^ + Delta m
     float mx2 = 0.0f;                                            // max |v| for the storage scale
 
-    if constexpr (SENDER) {
+    if constexpr (SENDER && kEB == 2) {
+        // ---- sixteen-bit activations: m^ stays, d = a - m^ is formed twice (one instruction
+        // per element from the activation as loaded), v takes m^'s registers ----------------------
+        float mx = 0.0f;
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            float d[kChunk];
+            stored_values<MBITS>(mw[k], msc, v[k]);      // v holds m^ for now
+            delta_from_values<DT>(ra[k], v[k], d);
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) mx = __builtin_fmaxf(mx, __builtin_fabsf(d[e]));
+        }
+        mx = team_max_all<TEAM, 0>(mx, wave_max);
+        const GroupScale sc = make_scale<BITS>(mx);
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) forget(ra[k]);     // d is formed again below, not kept
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            float r[kChunk];
+            if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
+                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r);
+            } else {
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e) r[e] = kNearestOffset32;
+            }
+            float d[kChunk], q[kChunk];
+            delta_from_values<DT>(ra[k], v[k], d);
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) {
+                q[e] = level_of<BITS, ROUND>(d[e], sc, r[e]);
+                v[k][e] = v[k][e] + value_of(q[e], sc);
+                mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
+            }
+            store_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS, pack_levels<BITS>(q));
+        }
+        if (lane_in_team == 0) scales_s[g] = sc.s_tx;
+    } else if constexpr (SENDER) {
         // ---- d = a - m^ and the wire scale ------------------------------------------------
         float d[CPL][kChunk];
         float mx = 0.0f;
@@ -162,6 +198,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
                 v[k][e] = m[e] + value_of(q[e], wsc);
                 mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
             }
+            __builtin_amdgcn_sched_barrier(0);           // one chunk's temporaries at a time
         }
     }
 

@@ -38,15 +38,15 @@ constexpr int kTopkBits = 8;
 constexpr int kTopkBins = 256;
 constexpr int kTopkStageBytes = kTopkMaxGroup + kWave;   // + one spare byte per lane for entries not kept
 
-// LDS of one wave.  (One histogram per row of 16 lanes, added up when read, was tried
-// against the bank conflicts of the counting: the conflicts are between different
-// counters of one bank, not lanes on one counter, and stayed; the extra clearing and
-// reading made the kernel slower.)
 // One wave per workgroup: a group is a wave's work and the waves share nothing, and with a
 // single TopkLds per workgroup every LDS address is an instruction offset instead of a
 // register sum (one vector instruction less per histogram update and per staged entry).
 constexpr int kTopkBlock = kWave;
 
+// LDS of one wave.  (One histogram per row of 16 lanes, added up when read, was tried
+// against the bank conflicts of the counting and did not remove them: 64 lanes updating
+// counters picked by the data fall several to a bank however the counters are laid out,
+// and the extra clearing and reading made the kernel slower.)
 struct TopkLds {
     uint32_t bins[kTopkBins + kWave];                    // 256 counters + one spare per lane
     uint8_t stage[kTopkStageBytes];
@@ -204,9 +204,9 @@ __device__ __forceinline__ void lanes_before(const uint32_t (&cnt)[CPL], int lan
 // only the entries that are kept.  The kernel is bound by vector arithmetic (a wave64
 // instruction occupies its SIMD for four cycles, and a group is a thousand of them in
 // the general path below), so instructions are what this path saves: no conversion of
-// all entries to binary32, no unpacked keys, digits of the radix select cut straight
-// out of the packed words, masks from the sign bits of packed differences, and one
-// quantisation per kept entry instead of one per entry.
+// all entries to binary32, no unpacked keys, each digit of the radix select a byte of
+// the packed word (magnitudes are held doubled for that), masks from the sign bits of
+// packed differences, and one quantisation per kept entry instead of one per entry.
 // ---------------------------------------------------------------------------
 typedef unsigned short u16x2_t __attribute__((ext_vector_type(2)));
 
