@@ -302,7 +302,7 @@ template <typename V>
 __global__ __launch_bounds__(kBlock)
 void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, int64_t units_per_row, int batch) {
     for (int i = blockIdx.y; i < batch; i += gridDim.y) {
-        const int64_t row = ids[i];
+        const int64_t row = sample_id(ids, i);
         const V* src = act + static_cast<int64_t>(i) * units_per_row;
         V* dst = m_buf + row * units_per_row;
         for (int64_t c = static_cast<int64_t>(blockIdx.x) * kBlock + threadIdx.x; c < units_per_row;

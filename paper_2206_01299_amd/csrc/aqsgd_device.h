@@ -233,6 +233,15 @@ __device__ __forceinline__ void store_elem(void* base, int64_t idx, float v) {
     else static_cast<uint16_t*>(base)[idx] = static_cast<uint16_t>(f32_to_bf16_bits(v));
 }
 
+// A call's sample ids are its input: nothing writes them while a kernel of the call runs.
+// Reading them as constant memory lets the compiler fetch an id with a scalar load (the
+// index is the same for every lane), which comes back sooner than a vector load does and
+// needs no readfirstlane; the row's loads can only be issued once the id is there.
+__device__ __forceinline__ int64_t sample_id(const int64_t* ids, int64_t i) {
+    typedef const int64_t __attribute__((address_space(4))) * constant_ids;
+    return reinterpret_cast<constant_ids>(reinterpret_cast<uintptr_t>(ids))[i];
+}
+
 // ---------------------------------------------------------------------------
 // Philox4x32-10 (Salmon et al., SC'11): counter-based, so element j of a call
 // gets the same draw whatever lane, wave or launch shape computes it.

@@ -288,7 +288,7 @@ __device__ __forceinline__ void quant_team_body(const QuantJob& a, uint32_t bx, 
     }
 
     for (int i = by; i < a.batch; i += a.grid_y) {
-        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        const int64_t row = a.ids ? sample_id(a.ids, i) : static_cast<int64_t>(i);
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;      // flat offset of sample i
         const char* src_s = static_cast<const char*>(a.src) + src0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
@@ -337,7 +337,7 @@ __device__ __forceinline__ void dequant_flat_body(const DequantJob& a, uint32_t 
     const float rcp_cpg = 1.0f / static_cast<float>(cpg);
     const uint32_t cps = static_cast<uint32_t>(a.cps);
     for (int i = by; i < a.batch; i += a.grid_y) {
-        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        const int64_t row = a.ids ? sample_id(a.ids, i) : static_cast<int64_t>(i);
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         char* out_s = static_cast<char*>(a.out) + out0 * kEB;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * kEB : nullptr;
@@ -426,7 +426,7 @@ __device__ __forceinline__ void dequant_units_body(const DequantJob& a, uint32_t
     const float rcp_upg = 1.0f / static_cast<float>(upg);
     const uint32_t ups = 2u * static_cast<uint32_t>(a.cps);              // units per sample
     for (int i = by; i < a.batch; i += a.grid_y) {
-        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        const int64_t row = a.ids ? sample_id(a.ids, i) : static_cast<int64_t>(i);
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         char* out_s = static_cast<char*>(a.out) + out0 * 4;
         char* m_s = HAS_BUF ? static_cast<char*>(a.m_buf) + row * a.n_per * 4 : nullptr;
@@ -668,7 +668,7 @@ void quant_anyshape_kernel(const QuantJob a, const int bits, const int rounding)
     const float hL = static_cast<float>(L) / 2.0f;
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
-        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        const int64_t row = a.ids ? sample_id(a.ids, i) : static_cast<int64_t>(i);
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
         bool fresh = false;
@@ -741,7 +741,7 @@ void dequant_anyshape_kernel(const DequantJob a) {
     const float hL = static_cast<float>(L) / 2.0f;
     const bool has_buf = a.m_buf != nullptr;
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
-        const int64_t row = a.ids ? a.ids[i] : static_cast<int64_t>(i);
+        const int64_t row = a.ids ? sample_id(a.ids, i) : static_cast<int64_t>(i);
         const int64_t out0 = static_cast<int64_t>(i) * a.n_per;
         const int64_t m0 = row * a.n_per;
         bool fresh = false;

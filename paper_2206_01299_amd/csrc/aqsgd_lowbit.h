@@ -76,11 +76,14 @@ __device__ __forceinline__ void stored_values(uint64_t mw, const GroupScale& msc
 }
 
 // One group.  The kernel is bound by vector arithmetic, not by memory (two quantisers and
-// a dequantiser per element), so nothing is computed twice except m^ on the sender: the
-// change d stays in registers across the first reduction and v across the second, and m^
-// is formed again from the stored levels when v is built, which keeps d, m^ and v from
-// being live all at once (that would cost a wave of occupancy per SIMD and with it the
-// chance to hold a whole launch on the chip at a time).
+// a dequantiser per element), and registers decide how many waves a SIMD holds, so what is
+// live across the two reductions is chosen by what is cheapest to form again.  Sender with
+// 16-bit activations: m^ stays in registers, the change d = a - m^ is formed for the first
+// reduction and again afterwards (one widening subtract per element from the activation as
+// loaded), and v = m^ + Delta m takes over m^'s registers.  Sender with binary32
+// activations: d stays across the first reduction and m^ is formed again from the stored
+// levels when v is built.  Keeping d, m^ and v live all at once would cost a wave of
+// occupancy per SIMD and with it the chance to hold a whole launch on the chip at a time.
 template <int DT, int BITS, int MBITS, int ROUND, int TEAM, int CPL, bool SENDER>
 __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const char* act_s, char* out_s,
                                                   uint8_t* mcodes_s, float* mscales_s, uint8_t* codes_s,
@@ -242,7 +245,7 @@ void lowbit_team_kernel(const LowbitArgs a) {
         cc[k] = static_cast<uint32_t>(min(k * TEAM + lane_in_team, a.cpg - 1));
 
     for (int i = blockIdx.y; i < a.batch; i += gridDim.y) {
-        const int64_t row = a.ids[i];
+        const int64_t row = sample_id(a.ids, i);
         const int64_t src0 = static_cast<int64_t>(i) * a.n_per;
         const char* act_s = SENDER ? static_cast<const char*>(a.act) + src0 * kEB : nullptr;
         char* out_s = SENDER ? nullptr : static_cast<char*>(a.out) + src0 * kEB;
