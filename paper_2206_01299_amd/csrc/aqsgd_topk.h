@@ -593,6 +593,18 @@ __device__ __forceinline__ void topk_dequant_group(const TopkArgs& a, int64_t g,
     wave_lds_sync();
 }
 
+// Workgroups are handed to the chip's eight XCDs in turn (workgroup b runs on XCD b % 8),
+// each with its own L2.  A group's bitmap and code bytes do not fill whole cache lines,
+// so neighbouring groups share lines: the numbering below gives every XCD one contiguous
+// run of the launch's workgroup slots, which keeps the two halves of such a line in one L2
+// (written back once) instead of in two.  A bijection of [0, n_blocks) for any n_blocks.
+constexpr uint32_t kXcds = 8;
+__device__ __forceinline__ uint32_t xcd_contiguous_slot(uint32_t block, uint32_t n_blocks) {
+    const uint32_t xcd = block % kXcds, turn = block / kXcds;
+    const uint32_t base = n_blocks / kXcds, extra = n_blocks % kXcds;     // the first `extra` XCDs get one more
+    return xcd * base + min(xcd, extra) + turn;
+}
+
 // MODE: 0 receiver, 1 sender with nearest rounding, 2 sender with stochastic rounding.
 template <int DT, int CPL, int MODE>
 __global__ __launch_bounds__(kTopkBlock)
@@ -602,6 +614,7 @@ void topk_kernel(const TopkArgs a) {
 
     const int lane = threadIdx.x % kWave;
     const int wave = kWaves == 1 ? 0 : __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+    const uint32_t slot = xcd_contiguous_slot(blockIdx.x, gridDim.x);
     uint32_t cc[CPL];
     bool valid[CPL];
 #pragma unroll
@@ -614,7 +627,7 @@ void topk_kernel(const TopkArgs a) {
         // The loads of the wave's first group go out before anything else: a launch is one
         // round of waves that all start by waiting for memory, and whatever does not depend
         // on the data (lane constants, clearing counters) is then worked off during that wait.
-        int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave;
+        int64_t g = static_cast<int64_t>(slot) * kWaves + wave;
         if (g >= a.n_groups) return;
         Raw<DT> raw[CPL];
         load_group16<DT, CPL>(a, g, cc, raw);
@@ -627,7 +640,7 @@ void topk_kernel(const TopkArgs a) {
         }
         return;
     }
-    for (int64_t g = static_cast<int64_t>(blockIdx.x) * kWaves + wave; g < a.n_groups;
+    for (int64_t g = static_cast<int64_t>(slot) * kWaves + wave; g < a.n_groups;
          g += static_cast<int64_t>(gridDim.x) * kWaves) {
         if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) { }
         else if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
