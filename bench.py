@@ -90,10 +90,11 @@ def parse_args():
     ap.add_argument("--steps", type=int, default=2048)
     ap.add_argument("--warmup", type=int, default=128)
     ap.add_argument("--launch", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--streams", type=int, choices=[0, 1, 2, 4, 8], default=0,
+    ap.add_argument("--streams", type=int, choices=[0, 1, 2, 3, 4, 6, 8], default=0,
                     help="streams the micro-batches are dealt over (they touch disjoint samples and pool "
-                         "slots, so their chains are independent); 0 = 2 for the fused schedules, 4 for "
-                         "`calls` (where half of the streams carry forward pairs and half backward pairs); "
+                         "slots, so their chains are independent); 0 = 2 for the fused schedules, 8 for "
+                         "`calls` (short single-message launches one after the other need more chains in "
+                         "flight to keep the memory system busy); "
                          "1: every launch strictly after the one before")
     ap.add_argument("--schedule", choices=["calls", "stage", "pipeline"], default="pipeline",
                     help="calls: four single-message calls per step; stage / pipeline: the same messages "
@@ -201,7 +202,6 @@ class Workload:
         self.ids = perm.view(-1, Bn).contiguous()              # [calls per epoch, B]
         self.calls = self.ids.shape[0]
         self.evict = torch.zeros(1 << 28, dtype=torch.int32, device=d)     # 1 GiB, see evict_caches()
-        self.events = []                                 # fork / join events of enqueue_steps, kept alive
         torch.cuda.synchronize()
 
     def _draw(self, shape):
@@ -350,30 +350,6 @@ class Workload:
             self.grad_quant(k)
             self.grad_dequant(k)
 
-    def make_streams(self, count=4):
-        """Streams of the four roles of a boundary: the sending stage encodes
-        activations and reconstructs gradients, the receiving stage decodes
-        activations and quantises gradients.  Default priority everywhere."""
-        torch = self.torch
-        self.streams = [torch.cuda.Stream() for _ in range(count)]
-
-    def step_on_streams(self, k, backward=True):
-        """The same four launches as step(): the forward pair on one stream, the
-        backward pair on another; consecutive micro-batches take different streams."""
-        torch = self.torch
-        if not backward:
-            with torch.cuda.stream(self.streams[k % len(self.streams)]):
-                self.encode(k)
-                self.decode(k)
-            return
-        half = len(self.streams) // 2
-        with torch.cuda.stream(self.streams[k % half]):
-            self.encode(k)
-            self.decode(k)
-        with torch.cuda.stream(self.streams[half + k % half]):
-            self.grad_quant(k)
-            self.grad_dequant(k)
-
     # -- algorithmic bytes per launch (what the method must move) ----------------
     def leg_bytes(self):
         c = self.cfg
@@ -437,6 +413,33 @@ class DeviceClock:
         wall = time.perf_counter() - t0 - hold_ms * 1e-3
         return a.elapsed_time(b) * 1e-3, wall
 
+    def time_streams(self, streams, enqueue, hold_ms=2.0):
+        """Independent work on several streams: enqueue(i) queues stream i's part on the
+        current stream.  Every stream waits for the end of one spin kernel (on
+        self.stream), stamps a start event, runs its part and stamps a stop event; the
+        region runs from the earliest start to the latest stop, so every kernel of every
+        stream lies inside it and no fork or join between streams does.  Returns (device
+        seconds, wall seconds)."""
+        torch = self.torch
+        ev = lambda: torch.cuda.Event(enable_timing=True)
+        starts, stops = [ev() for _ in streams], [ev() for _ in streams]
+        opened = torch.cuda.Event()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        with torch.cuda.stream(self.stream):
+            torch.cuda._sleep(int(hold_ms * self.cycles_per_ms))
+            opened.record(self.stream)
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                st.wait_event(opened)
+                starts[i].record(st)
+                enqueue(i)
+                stops[i].record(st)
+        torch.cuda.synchronize()
+        wall = time.perf_counter() - t0 - hold_ms * 1e-3
+        first = min(range(len(streams)), key=lambda i: starts[0].elapsed_time(starts[i]))
+        return max(starts[first].elapsed_time(b) for b in stops) * 1e-3, wall
+
 
 def evict_caches(torch, scratch, footprint_bytes):
     """Make sure the next kernels find none of their rows cached.  A region that itself
@@ -449,76 +452,56 @@ def evict_caches(torch, scratch, footprint_bytes):
     torch.cuda.synchronize()
 
 
-def enqueue_steps(wl, main, k0, k1, n_streams, schedule, backward=True):
-    """Steps k0..k1-1 onto `main` (one stream), or fanned out from / joined back into it
-    (wl.make_streams(n_streams) made the streams; micro-batches are dealt round-robin)."""
-    torch = wl.torch
-    if n_streams == 1:
-        with torch.cuda.stream(main):
-            if schedule == "calls":
-                for k in range(k0, k1):
-                    wl.step(k, backward)
-            else:
-                wl.fused_chain(list(range(k0, k1)), schedule, backward)
+def stream_part(wl, i, n_streams, k0, k1, schedule, backward=True):
+    """Queues on the current stream what stream i of n_streams does of steps k0..k1-1.
+    Micro-batches touch disjoint samples and buffers, so the streams' parts are
+    independent of each other: stream i takes the micro-batches k0+i, k0+i+n, ... — as one
+    chain of fused launches, or as their single calls one after the other."""
+    ks = list(range(k0 + i, k1, n_streams))
+    if schedule != "calls":
+        wl.fused_chain(ks, schedule, backward)
         return
-    # The fork and join events outlive this call (wl.events): inside a graph capture an
-    # event that is destroyed before the capture ends is still on the capturing stream's
-    # books, and the runtime touching it afterwards has corrupted the host heap here.
-    fork = torch.cuda.Event()
-    wl.events.append(fork)
-    fork.record(main)
-    for st in wl.streams:
-        st.wait_event(fork)
-    if schedule == "calls":
-        for k in range(k0, k1):
-            wl.step_on_streams(k, backward)
-    else:
-        for i, st in enumerate(wl.streams):
-            with torch.cuda.stream(st):
-                wl.fused_chain(list(range(k0 + i, k1, n_streams)), schedule, backward)
-    for st in wl.streams:
-        done = torch.cuda.Event()
-        wl.events.append(done)
-        done.record(st)
-        main.wait_event(done)
+    for k in ks:
+        wl.step(k, backward)
 
 
 def timed_steps(wl, first, count, launch, n_streams, backward=True, schedule="calls"):
     """Run `count` steps starting at step index `first`; returns (device seconds, wall
-    seconds) of the whole region.  In graph mode the graphs are built, instantiated and
-    replayed once before the clock starts (the first replay of a new graph uploads it);
-    the caches are then evicted, so the timed replay reads cold rows again."""
+    seconds) of the whole region.  Each stream's part is recorded into HIP graphs of its
+    own (one stream per capture, nothing between streams inside a graph); the graphs are
+    built, instantiated and replayed once before the clock starts (the first replay of a
+    new graph uploads it); the caches are then evicted, so the timed replay reads cold rows
+    again.  The clock is DeviceClock.time_streams."""
     torch = wl.torch
-    main = torch.cuda.Stream()
-    if n_streams > 1:
-        wl.make_streams(n_streams)
-    clock = DeviceClock(torch, main)
-
-    def enqueue(k0, k1):
-        enqueue_steps(wl, main, k0, k1, n_streams, schedule, backward)
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    clock = DeviceClock(torch, torch.cuda.Stream())
 
     if launch == "eager":
         # the spin must outlast the host's enqueueing of every launch (about 10 us each)
-        return clock.time(lambda: enqueue(first, first + count), hold_ms=2.0 + 0.05 * count)
-    graphs = []
+        return clock.time_streams(
+            streams, lambda i: stream_part(wl, i, n_streams, first, first + count, schedule, backward),
+            hold_ms=2.0 + 0.05 * count)
+    graphs = [[] for _ in streams]
     k = first
     while k < first + count:
         m = min(GRAPH_STEPS, first + count - k)
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g, stream=main):
-            enqueue(k, k + m)
-        graphs.append(g)
+        # a multiple of the stream count per graph keeps every stream's share of a graph the same
+        for i, st in enumerate(streams):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=st):
+                stream_part(wl, i, n_streams, k, k + m, schedule, backward)
+            graphs[i].append(g)
         k += m
-    with torch.cuda.stream(main):
-        for g in graphs:                                 # untimed: uploads the graphs
+
+    def replay(i):
+        for g in graphs[i]:
             g.replay()
+    for i, st in enumerate(streams):                     # untimed: uploads the graphs
+        with torch.cuda.stream(st):
+            replay(i)
     lb = wl.leg_bytes()
     evict_caches(torch, wl.evict, count * sum(lb[l] for l in (wl.LEGS if backward else wl.LEGS[:2])))
-
-    def replay_all():
-        for g in graphs:
-            g.replay()
-    return clock.time(replay_all)
+    return clock.time_streams(streams, replay)
 
 
 def hot_forward_pairs(wl, k, count):
@@ -930,7 +913,7 @@ def main():
     if args.m_bits or args.bwd_keep:
         sched = "calls"                                  # these variants have single-message calls only
     if args.streams == 0:
-        args.streams = 4 if sched == "calls" else 2
+        args.streams = 8 if sched == "calls" else 2
     step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams, schedule=sched)
     fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False, schedule=sched)
     ms_per_step = step_dev / K * 1e3
@@ -1016,10 +999,12 @@ def main():
                                "(the metric's quantity), from a second timed run of the same K "
                                "micro-batches without the backward message; the whole step is under "
                                "whole_step",
-                   "timing": "HIP events on the launching stream around the replays of HIP graphs that "
-                             "were instantiated and replayed once beforehand, queued behind a spin kernel "
-                             "so that host launch latency is outside the bracket; caches evicted before "
-                             "the timed replay; every kernel of all K steps is inside",
+                   "timing": "each stream's chain of micro-batches is a sequence of HIP graphs of its own, "
+                             "instantiated and replayed once beforehand; all streams wait for the end of one "
+                             "spin kernel (host launch latency stays outside), each stamps a HIP event before "
+                             "and after its replays, and the region runs from the earliest start stamp to the "
+                             "latest stop stamp; caches evicted before the timed replay; every kernel of all "
+                             "K steps is inside",
                    "storage_dtype": cfg.dtype, "batch": cfg.batch, "seq": cfg.seq, "hidden": cfg.hidden,
                    "n_samples": cfg.n_samples, "fwd_bits": cfg.fwd_bits, "bwd_bits": cfg.bwd_bits,
                    "group": cfg.fwd_group, "m_bits": args.m_bits or None, "bwd_keep": args.bwd_keep or None,

@@ -1,10 +1,10 @@
 """Parity in the launch configurations that bench.py times: the GPT2-1.5B-shaped
 boundary at full size (8192-sample buffers, float16 [4, 1024, 1600] micro-batches),
-steps recorded into a HIP graph with bench.py's own enqueueing code and replayed twice:
-the default (one launch per time slot of the two stages, micro-batches dealt over two
-streams), the per-stage launches, and the four single calls on four streams.  Every
-output of every step, and every visited row of both copies of m, must equal the oracle's
-after each replay."""
+every stream's part of the steps recorded into a HIP graph of its own with bench.py's own
+enqueueing code, and the graphs replayed twice on their streams: the default (one launch
+per time slot of the two stages, micro-batches dealt over two streams), the per-stage
+launches, and the four single calls on four streams.  Every output of every step, and
+every visited row of both copies of m, must equal the oracle's after each replay."""
 import numpy as np
 import pytest
 import torch
@@ -25,12 +25,13 @@ def test_graph_at_full_size_matches_the_oracle(schedule, n_streams):
     cfg = W.gpt2_4bit()
     steps = 8
     wl = bench.Workload(cfg, pool=steps)                 # m starts at zero: replay 1 = first visits
-    if n_streams > 1:
-        wl.make_streams(n_streams)
-    main = torch.cuda.Stream()
-    graph = torch.cuda.CUDAGraph()
-    with torch.cuda.graph(graph, stream=main):           # the enqueueing code of bench.timed_steps
-        bench.enqueue_steps(wl, main, 0, steps, n_streams, schedule)
+    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    graphs = []
+    for i, st in enumerate(streams):                     # the enqueueing code of bench.timed_steps
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=st):
+            bench.stream_part(wl, i, n_streams, 0, steps, schedule)
+        graphs.append(g)
     torch.cuda.synchronize()
     assert not bool(wl.m_send[wl.ids[0]].any())          # capture ran nothing
 
@@ -39,7 +40,9 @@ def test_graph_at_full_size_matches_the_oracle(schedule, n_streams):
     grads = [W.from_torch(wl.grad[k], cfg.dtype).reshape(cfg.batch, cfg.n_per) for k in range(steps)]
     cpu = H.OracleBoundary(cfg, ids.reshape(-1))
     for replay in range(2):
-        graph.replay()
+        for g, st in zip(graphs, streams):
+            with torch.cuda.stream(st):
+                g.replay()
         torch.cuda.synchronize()
         for k in range(steps):
             want = cpu.forward(acts[k], ids[k], 0)
