@@ -623,29 +623,28 @@ void topk_kernel(const TopkArgs a) {
         valid[k] = c < a.cpg;
         cc[k] = static_cast<uint32_t>(min(c, a.cpg - 1));
     }
+    const int64_t stride = static_cast<int64_t>(gridDim.x) * kWaves;
+    int64_t g = static_cast<int64_t>(slot) * kWaves + wave;
     if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) {
         // The loads of the wave's first group go out before anything else: a launch is one
         // round of waves that all start by waiting for memory, and whatever does not depend
         // on the data (lane constants, clearing counters) is then worked off during that wait.
-        int64_t g = static_cast<int64_t>(slot) * kWaves + wave;
         if (g >= a.n_groups) return;
         Raw<DT> raw[CPL];
         load_group16<DT, CPL>(a, g, cc, raw);
         __builtin_amdgcn_sched_barrier(0);
         for (;;) {
             topk_quant_group16<DT, CPL>(a, g, raw, cc, valid, lane, lds_all[wave]);
-            g += static_cast<int64_t>(gridDim.x) * kWaves;
+            g += stride;
             if (g >= a.n_groups) break;
             load_group16<DT, CPL>(a, g, cc, raw);
         }
-        return;
-    }
-    for (int64_t g = static_cast<int64_t>(slot) * kWaves + wave; g < a.n_groups;
-         g += static_cast<int64_t>(gridDim.x) * kWaves) {
-        if constexpr (MODE == 1 && KeyBytes<DT>::value == 2) { }
-        else if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
-        else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
-        else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+    } else {
+        for (; g < a.n_groups; g += stride) {
+            if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
+            else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
+            else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
+        }
     }
 }
 

@@ -70,7 +70,8 @@ def _run(H, dtype, group, keep, n_groups, kind, rounding=0, seed=1, batch=1):
     assert H.same_bytes(got, wo), f"{tag}: out: {H.first_diff(got, wo)}"
 
 
-SHAPES = [(8, 1), (8, 8), (64, 13), (128, 26), (512, 112), (520, 104), (1024, 208), (1600, 320), (2048, 411)]
+SHAPES = [(8, 1), (8, 8), (64, 13), (128, 26), (512, 112), (520, 104), (1024, 208), (1600, 320), (2048, 411),
+          (1600, 1), (1600, 1599), (1600, 1600), (2048, 1), (2048, 2048)]    # nothing but the largest; (nearly) everything
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
