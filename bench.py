@@ -123,6 +123,10 @@ def parse_args():
                     help="secondary line: what this GPU does with launches of this size: a near-empty "
                          "launch, the library's plain row copy and its encode / decode at growing "
                          "micro-batch sizes, and large fill / copy kernels")
+    ap.add_argument("--region-sweep", action="store_true",
+                    help="secondary line: the timed region at 10, 20, 40, 80, 160 and 320 steps in one process "
+                         "(whole step and forward messages alone), to show what the length of the region "
+                         "does to the per-step figures")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
                          "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
@@ -441,6 +445,46 @@ class DeviceClock:
         return max(starts[first].elapsed_time(b) for b in stops) * 1e-3, wall
 
 
+_SIDE_BY_SIDE = {}
+
+
+def side_by_side_streams(torch, n):
+    """n streams whose kernels really run next to each other, the same ones for every timed
+    region of the process.  A process has a few hardware queues and the runtime spreads its
+    streams over them; two streams that share a queue take turns, and which streams of
+    torch's pool do so depends on how many were handed out before (regions timed later in
+    a process were 14 % slower for that reason alone).  So candidates are tried in pairs
+    with two spin kernels and a stream is taken only if it overlaps with those already
+    taken.  More streams than hardware queues cannot all overlap: past four, streams are
+    taken as they come."""
+    have = _SIDE_BY_SIDE.setdefault("streams", [])
+    if "cycles_per_ms" not in _SIDE_BY_SIDE:
+        _SIDE_BY_SIDE["cycles_per_ms"] = DeviceClock(torch, torch.cuda.Stream()).cycles_per_ms
+    spin = int(0.3 * _SIDE_BY_SIDE["cycles_per_ms"])
+
+    def overlap(a, b):
+        s, ea, eb = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+        torch.cuda.synchronize()
+        s.record(a)
+        b.wait_event(s)
+        with torch.cuda.stream(a):
+            torch.cuda._sleep(spin)
+            ea.record(a)
+        with torch.cuda.stream(b):
+            torch.cuda._sleep(spin)
+            eb.record(b)
+        torch.cuda.synchronize()
+        return max(s.elapsed_time(ea), s.elapsed_time(eb)) < 0.3 * 1.5
+
+    tries = 0
+    while len(have) < n:
+        c = torch.cuda.Stream()
+        tries += 1
+        if len(have) >= 4 or tries > 64 or all(overlap(h, c) for h in have):
+            have.append(c)
+    return have[:n]
+
+
 def evict_caches(torch, scratch, footprint_bytes):
     """Make sure the next kernels find none of their rows cached.  A region that itself
     touches more than 1 GiB of distinct rows (four times the last-level cache) has evicted
@@ -473,7 +517,7 @@ def timed_steps(wl, first, count, launch, n_streams, backward=True, schedule="ca
     new graph uploads it); the caches are then evicted, so the timed replay reads cold rows
     again.  The clock is DeviceClock.time_streams."""
     torch = wl.torch
-    streams = [torch.cuda.Stream() for _ in range(n_streams)]
+    streams = side_by_side_streams(torch, n_streams)
     clock = DeviceClock(torch, torch.cuda.Stream())
 
     if launch == "eager":
@@ -862,6 +906,33 @@ def ceilings_line(args, cfg, wl):
     print(json.dumps(line))
 
 
+def region_sweep_line(args, cfg, wl, sched, n_streams):
+    """The timed region at growing step counts, same process, same schedule and streams."""
+    for k in range(16):
+        wl.step(k)
+    wl.torch.cuda.synchronize()
+    rows = []
+    for K in (10, 20, 40, 80, 160, 320):
+        step = [timed_steps(wl, 16, K, args.launch, n_streams, schedule=sched)[0] for _ in range(3)]
+        fwd = [timed_steps(wl, 16, K, args.launch, n_streams, backward=False, schedule=sched)[0] for _ in range(3)]
+        step.sort(); fwd.sort()
+        rows.append({"steps": K, "step_region_us": round(step[1] * 1e6, 1), "us_per_step": round(step[1] / K * 1e6, 3),
+                     "fwd_region_us": round(fwd[1] * 1e6, 1), "us_per_fwd_pair": round(fwd[1] / K * 1e6, 3)})
+    act_bytes = cfg.n * cfg.elem_bytes
+    line = {
+        "metric": "timed region length sweep: device time of K steps and of their forward messages alone",
+        "value": round(act_bytes / (rows[-1]["us_per_fwd_pair"] * 1e-6) / 1e9, 1), "unit": "GB/s",
+        "n_gpus": 1, "steps": rows[-1]["steps"], "warmup": 16, "ms_per_step": round(rows[-1]["us_per_step"] * 1e-3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": WORKLOAD_TEXT[args.config] + "; region-length sweep", "schedule": sched,
+                   "streams": n_streams, "launch": args.launch,
+                   "value_is": "activation GB/s of encode + decode at the longest region",
+                   "method": "median of three timed regions per length, the clock of the headline line"},
+        "region_sweep": rows, "roofline": None, "cpu_baseline": None,
+    }
+    print(json.dumps(line))
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -914,6 +985,9 @@ def main():
         sched = "calls"                                  # these variants have single-message calls only
     if args.streams == 0:
         args.streams = 8 if sched == "calls" else 2
+    if args.region_sweep:
+        region_sweep_line(args, cfg, wl, sched, args.streams)
+        return
     step_dev, step_wall = timed_steps(wl, Wm, K, args.launch, args.streams, schedule=sched)
     fwd_dev, fwd_wall = timed_steps(wl, Wm, K, args.launch, args.streams, backward=False, schedule=sched)
     ms_per_step = step_dev / K * 1e3
