@@ -37,6 +37,21 @@ def _gradient(n, seed, dtype, kind):
         g[rng.random(n) < 0.9] = 0.0
         g[: n // 4] = 0.0
         g[::7] *= -1.0                                # some of the zeros are negative zeros
+    elif kind == "edge":                              # one kind of degenerate group after the other
+        big = {"f16": 65504.0, "bf16": 3.3895e38, "f32": 3.4028e38}[dtype]
+        tiny = {"f16": 2.0 ** -24, "bf16": 2.0 ** -133, "f32": 2.0 ** -149}[dtype]
+        g = np.zeros(n, dtype=np.float64)
+        G = n // 8
+        j = np.arange(G)
+        g[0 * G:1 * G] = 0.75                                        # every magnitude equal
+        g[1 * G:2 * G] = np.where(j % 2 == 0, 0.75, -0.75)           # ... with mixed signs
+        g[2 * G + G // 3] = -1e-3                                    # a single non-zero entry
+        g[3 * G:4 * G] = 1.0 + (j % 97) * 2.0 ** -7                  # one leading byte, close low bits
+        g[4 * G:5 * G] = np.where(j % 3 == 0, big, -big / 2)         # the largest finite values
+        g[5 * G:6 * G] = (j % 50) * tiny                             # subnormal magnitudes and zeros
+        g[6 * G:7 * G] = (G - j) * 1e-2                              # descending
+        g[7 * G:8 * G] = -(j + 1) * 1e-2                             # ascending magnitudes, negative
+        g = g.astype(np.float32)
     else:
         raise ValueError(kind)
     return W.to_storage(g, dtype)
@@ -79,6 +94,14 @@ SHAPES = [(8, 1), (8, 8), (64, 13), (128, 26), (512, 112), (520, 104), (1024, 20
 def test_topk_matches_oracle(H, dtype, group, keep):
     for kind in ("heavy", "ties", "sparse"):
         _run(H, dtype, group, keep, n_groups=13, kind=kind)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_topk_degenerate_groups(H, dtype):
+    """Eight groups, each degenerate in its own way (all equal, a single entry, one leading
+    byte, the largest finite values, subnormals, sorted either way)."""
+    for group, keep in ((1600, 320), (64, 13), (2048, 1), (512, 511)):
+        _run(H, dtype, group, keep, n_groups=8, kind="edge")
 
 
 @pytest.mark.parametrize("dtype", ["f16", "f32"])
