@@ -105,6 +105,18 @@ def test_lowbit_sweep(H, dtype, m_bits):
             _replay(H, _cfg(dtype, bits, group, rounding, gps), m_bits, calls_per_epoch=2, epochs=2)
 
 
+@pytest.mark.parametrize("dtype,scale", [("f16", 3e-7), ("f16", 2e-5), ("bf16", 1e-37), ("f32", 1e-36)])
+@pytest.mark.parametrize("m_bits", [2, 8])
+def test_lowbit_subnormal_activations(H, dtype, scale, m_bits):
+    """Activations in and just above the storage type's subnormal range (float16), and around
+    the 2^-120 floor below which a group is sent as zero (bfloat16, binary32): widening,
+    differences and sums must not flush anything to zero."""
+    for group, bits in ((1600, 4), (64, 8), (128, 2)):
+        cfg = _cfg(dtype, bits, group, W.NEAREST, gps=9).scaled(outlier_channel_frac=1.0, outlier_scale=scale,
+                                                                  name=f"lowbit_small_{dtype}_{scale}_g{group}")
+        _replay(H, cfg, m_bits, calls_per_epoch=2, epochs=2)
+
+
 def test_lowbit_rejects_what_it_does_not_support(H):
     import ctypes
     L = B.lib()
