@@ -462,19 +462,22 @@ def side_by_side_streams(torch, n):
         _SIDE_BY_SIDE["cycles_per_ms"] = DeviceClock(torch, torch.cuda.Stream()).cycles_per_ms
     spin = int(0.3 * _SIDE_BY_SIDE["cycles_per_ms"])
 
+    def spin_ms(streams_):
+        """Device time from a common start to the end of one spin kernel per stream."""
+        s0 = torch.cuda.Event(enable_timing=True)
+        ends = [torch.cuda.Event(enable_timing=True) for _ in streams_]
+        torch.cuda.synchronize()
+        s0.record(streams_[0])
+        for st, e in zip(streams_, ends):
+            st.wait_event(s0)
+            with torch.cuda.stream(st):
+                torch.cuda._sleep(spin)
+                e.record(st)
+        torch.cuda.synchronize()
+        return max(s0.elapsed_time(e) for e in ends)
+
     def overlap(a, b):
-        s, ea, eb = (torch.cuda.Event(enable_timing=True) for _ in range(3))
-        torch.cuda.synchronize()
-        s.record(a)
-        b.wait_event(s)
-        with torch.cuda.stream(a):
-            torch.cuda._sleep(spin)
-            ea.record(a)
-        with torch.cuda.stream(b):
-            torch.cuda._sleep(spin)
-            eb.record(b)
-        torch.cuda.synchronize()
-        return max(s.elapsed_time(ea), s.elapsed_time(eb)) < 0.3 * 1.5
+        return spin_ms([a, b]) < 1.5 * spin_ms([a])
 
     tries = 0
     while len(have) < n:
@@ -1088,6 +1091,7 @@ def main():
                    "group": cfg.fwd_group, "m_bits": args.m_bits or None, "bwd_keep": args.bwd_keep or None,
                    "pool_slots": args.pool, "launch": args.launch, "schedule": sched,
                    "streams": args.streams,
+                   "streams_checked_to_overlap": args.streams in (2, 3, 4),
                    "cold_buffers": True, "device": torch.cuda.get_device_name(0),
                    "setup_s": round(t_setup, 1)},
         "roofline": roofline, "cpu_baseline": base,
