@@ -246,6 +246,12 @@ __device__ __forceinline__ int64_t sample_id(const int64_t* ids, int64_t i) {
 // Philox4x32-10 (Salmon et al., SC'11): counter-based, so element j of a call
 // gets the same draw whatever lane, wave or launch shape computes it.
 // ---------------------------------------------------------------------------
+// a ^ b ^ c in one instruction (v_bitop3_b32 with the truth table of a three-input xor;
+// the compiler does not form it from two xors by itself).
+__device__ __forceinline__ uint32_t xor3(uint32_t a, uint32_t b, uint32_t c) {
+    return __builtin_amdgcn_bitop3_b32(a, b, c, 0x96);
+}
+
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t k0, uint32_t k1,
                                               uint32_t (&out)[4]) {
     uint32_t c2 = 0u, c3 = 0u;
@@ -253,9 +259,9 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     for (int round = 0; round < 10; ++round) {
         const uint64_t p0 = static_cast<uint64_t>(0xD2511F53u) * c0;
         const uint64_t p1 = static_cast<uint64_t>(0xCD9E8D57u) * c2;
-        const uint32_t n0 = static_cast<uint32_t>(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n0 = xor3(static_cast<uint32_t>(p1 >> 32), c1, k0);
         const uint32_t n1 = static_cast<uint32_t>(p1);
-        const uint32_t n2 = static_cast<uint32_t>(p0 >> 32) ^ c3 ^ k1;
+        const uint32_t n2 = xor3(static_cast<uint32_t>(p0 >> 32), c3, k1);
         const uint32_t n3 = static_cast<uint32_t>(p0);
         c0 = n0; c1 = n1; c2 = n2; c3 = n3;
         k0 += 0x9E3779B9u;
