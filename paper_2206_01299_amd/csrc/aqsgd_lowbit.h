@@ -94,6 +94,9 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
     constexpr int kChunkBytes = kChunk * kEB;
     const int64_t goff = g * a.group;                    // element offset within the sample
     const int64_t gchunk = goff / kChunk;
+    // the group's own pointers (uniform over the team) + a lane's 32-bit byte offsets
+    uint8_t* const m_group = mcodes_s + gchunk * MBITS;
+    uint8_t* const c_group = codes_s + gchunk * BITS;
 
     // ---- issue every load of the group ------------------------------------------
     uint64_t mw[CPL], cw[CPL];
@@ -103,9 +106,9 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
     if constexpr (!SENDER) wire_scale = scales_s[g];
 #pragma unroll
     for (int k = 0; k < CPL; ++k) {
-        mw[k] = load_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS);
+        mw[k] = load_codes_at<MBITS>(m_group + cc[k] * static_cast<uint32_t>(MBITS));
         if constexpr (SENDER) ra[k] = load_raw_at<DT>(act_s + goff * kEB + cc[k] * kChunkBytes);
-        else cw[k] = load_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS);
+        else cw[k] = load_codes_at<BITS>(c_group + cc[k] * static_cast<uint32_t>(BITS));
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -146,7 +149,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
                 v[k][e] = v[k][e] + value_of(q[e], sc);
                 mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
             }
-            store_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS, pack_levels<BITS>(q));
+            store_codes_at<BITS>(c_group + cc[k] * static_cast<uint32_t>(BITS), pack_levels<BITS>(q));
         }
         if (lane_in_team == 0) scales_s[g] = sc.s_tx;
     } else if constexpr (SENDER) {
@@ -186,7 +189,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
                 v[k][e] = m[e] + value_of(q[e], sc);
                 mx2 = __builtin_fmaxf(mx2, __builtin_fabsf(v[k][e]));
             }
-            store_codes_at<BITS>(codes_s + (gchunk + cc[k]) * BITS, pack_levels<BITS>(q));
+            store_codes_at<BITS>(c_group + cc[k] * static_cast<uint32_t>(BITS), pack_levels<BITS>(q));
         }
         if (lane_in_team == 0) scales_s[g] = sc.s_tx;
     } else {
@@ -213,7 +216,7 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
         float q2[kChunk];
 #pragma unroll
         for (int e = 0; e < kChunk; ++e) q2[e] = level_of<MBITS, AQSGD_ROUND_NEAREST>(v[k][e], ssc, kNearestOffset32);
-        store_codes_at<MBITS>(mcodes_s + (gchunk + cc[k]) * MBITS, pack_levels<MBITS>(q2));
+        store_codes_at<MBITS>(m_group + cc[k] * static_cast<uint32_t>(MBITS), pack_levels<MBITS>(q2));
         if constexpr (!SENDER) store_raw_at<DT>(out_s + goff * kEB + cc[k] * kChunkBytes, pack_raw<DT>(v[k]));
     }
     if (lane_in_team == 0) mscales_s[g] = ssc.s_tx;
