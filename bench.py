@@ -612,7 +612,7 @@ def kernel_legs(wl, first, count, schedule="calls"):
     count = min(count, 1024)
     fused = {}
     one_launch = (wl.cfg.fwd_rounding == wl.cfg.bwd_rounding and wl.cfg.fwd_group == wl.cfg.bwd_group
-                  and (wl.cfg.fwd_bits == 3) == (wl.cfg.bwd_bits == 3) and not wl.m_bits and not wl.keep)
+                  and not wl.m_bits and not wl.keep)
     if schedule == "stage" and not wl.m_bits and not wl.keep:
         fused = {"sender_launch(encode+grad_dequant)": ("encode", "grad_dequant"),
                  "receiver_launch(decode+grad_quant)": ("decode", "grad_quant")}

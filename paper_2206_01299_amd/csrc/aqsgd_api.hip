@@ -207,7 +207,7 @@ DequantPlan plan_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, cons
 }
 
 // The launches of a set of independent messages: quantising jobs that share dtype,
-// rounding mode, team shape and bit-width class (3 bits or not) go into one grid, together with the dequantising
+// rounding mode and team shape go into one grid, together with the dequantising
 // jobs of that dtype that are still waiting; dequantising jobs without such a host get a
 // grid of their own; jobs that need the any-shape kernels are launched one by one.
 int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipStream_t stream) {
@@ -244,11 +244,12 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         JobTable t;
         t.n_quant = t.n_dequant = 0;
         int64_t blocks = 0;
+        bool three = false;                              // a 3-bit job among them: the kernel variant that has those bodies
         for (size_t k = i; k < qs.size() && t.n_quant < kMaxQuantJobs; ++k) {
             const QuantPlan& c = qs[k];
-            if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.rounding != lead.rounding ||
-                (c.bits == 3) != (lead.bits == 3))
+            if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.rounding != lead.rounding)
                 continue;
+            three = three || c.bits == 3;
             QuantJob a = c.job;
             const LaunchGeom g = geometry(a.gps, teams_per_block(c.shape), a.batch, max_blocks);
             a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
@@ -260,7 +261,7 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         t.dequant_block0 = static_cast<uint32_t>(blocks);
         add_dequant(t, lead.dtype, threads_of_shape(lead.shape), kHostedDequantUnroll, blocks);
         t.total_blocks = static_cast<uint32_t>(blocks);
-        err = launch_codec_jobs(lead.dtype, lead.rounding, lead.shape, lead.bits == 3, t, stream);
+        err = launch_codec_jobs(lead.dtype, lead.rounding, lead.shape, three, t, stream);
     }
     for (size_t i = 0; i < ds.size() && err == hipSuccess; ++i) {
         if (d_done[i]) continue;

@@ -590,8 +590,10 @@ constexpr int kHostedDequantUnroll = 2;      // dequantising jobs inside a quant
 // One quantising job in a team kernel: the body for its bit width and for with /
 // without previous messages.  The 3-bit bodies (codes leave through a lane
 // transpose) need a sixth more registers than the others, which would cost every
-// launch a wave of occupancy per SIMD, so they live in a kernel of their own:
-// THREE selects between the bodies for 3 bits and those for 2, 4, 6 and 8.
+// launch a wave of occupancy per SIMD, so the kernel comes in two variants: without
+// them (THREE = false: 2, 4, 6 and 8 bits), and with them for a table in which at
+// least one quantising job is 3-bit (THREE = true: every width, at the 3-bit bodies'
+// register count).
 template <int DT, int BITS, int ROUND, int TEAM, int CPL>
 __device__ __forceinline__ void quant_job_bits(const QuantJob& a, uint32_t bx, uint32_t by, float* wave_max) {
     if (a.m_buf) quant_team_body<DT, BITS, ROUND, TEAM, CPL, true>(a, bx, by, wave_max);
@@ -601,19 +603,21 @@ __device__ __forceinline__ void quant_job_bits(const QuantJob& a, uint32_t bx, u
 template <int DT, int ROUND, int TEAM, int CPL, bool THREE>
 __device__ __forceinline__ void quant_job(const QuantJob& a, uint32_t bx, uint32_t by, float* wave_max) {
     if constexpr (THREE) {
-        quant_job_bits<DT, 3, ROUND, TEAM, CPL>(a, bx, by, wave_max);
-    } else {
-        switch (a.bits) {                                // uniform over the workgroup
-        case 2: quant_job_bits<DT, 2, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
-        case 4: quant_job_bits<DT, 4, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
-        case 6: quant_job_bits<DT, 6, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
-        default: quant_job_bits<DT, 8, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+        if (a.bits == 3) {                               // uniform over the workgroup
+            quant_job_bits<DT, 3, ROUND, TEAM, CPL>(a, bx, by, wave_max);
+            return;
         }
+    }
+    switch (a.bits) {
+    case 2: quant_job_bits<DT, 2, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+    case 4: quant_job_bits<DT, 4, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+    case 6: quant_job_bits<DT, 6, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
+    default: quant_job_bits<DT, 8, ROUND, TEAM, CPL>(a, bx, by, wave_max); break;
     }
 }
 
-// The quantising jobs of one rounding mode, team shape and bit-width class (3 bits, or
-// any of the others) plus any dequantising jobs.
+// The quantising jobs of one rounding mode and team shape (THREE: 3-bit ones among them)
+// plus any dequantising jobs.
 template <int DT, int ROUND, int TEAM, int CPL, bool THREE>
 __global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock))
 void codec_jobs_kernel(const JobTable t) {
@@ -825,8 +829,8 @@ enum TeamShape {
 };
 
 // A launch of codec_jobs_kernel (the table's quantising jobs all have this rounding
-// mode and team shape, and are either all 3-bit or all not) or, with no quantising job,
-// of dequant_jobs_kernel.
+// mode and team shape; `three`: at least one of them is 3-bit) or, with no quantising
+// job, of dequant_jobs_kernel.
 hipError_t launch_codec_jobs(int dtype, int rounding, int shape, bool three, const JobTable& t,
                              hipStream_t stream);
 hipError_t launch_dequant_jobs(int dtype, int unroll, const JobTable& t, hipStream_t stream);

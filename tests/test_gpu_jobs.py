@@ -75,7 +75,7 @@ class Boundary:
         import oracle
         codes, scales, ids, wc, ws, ids_np = self.wire
         out = self._dev(W.to_storage(np.full((self.batch, self.n_per), 9.0, dtype=np.float32), self.dtype))
-        self.keep.append(out)
+        self.keep += [out, codes, scales, ids]            # a later encode_job replaces self.wire
         wo = oracle.decode(wc, ws, ids_np, self.om_r, dtype=self.dtype, bits=self.fb, group=self.fg)
         self.checks.append(("decode out", out, wo))
         return B.decode_job(self.fdesc, codes, scales, ids, self.m_r, out)
@@ -99,7 +99,7 @@ class Boundary:
         import oracle
         codes, scales, wc, ws = self.gwire
         out = self._dev(W.to_storage(np.full((self.batch, self.n_per), 7.0, dtype=np.float32), self.dtype))
-        self.keep.append(out)
+        self.keep += [out, codes, scales]                 # a later grad_quant_job replaces self.gwire
         wo = oracle.grad_dequant(wc, ws, dtype=self.dtype, bits=self.bb, group=self.bg)
         self.checks.append(("grad_dequant out", out, wo))
         return B.grad_dequant_job(self.bdesc, codes, scales, out)
@@ -162,6 +162,39 @@ def test_eight_boundaries_with_mixed_bits_in_one_call(H):
         B.run_jobs([b.grad_dequant_job() for b in bs])
         for i, b in enumerate(bs):
             b.verify(f"boundary {i} step {step}")
+
+
+THREE_MIXES = [
+    # dtype, group, rounding, forward bits of the boundaries, backward bits, batch, groups per sample
+    ("bf16", 64, 0, (3, 4, 3), 6, 5, 517),               # the DeBERTa boundary's widths, 8-lane teams
+    ("f16", 1600, 0, (3, 8), 2, 2, 37),                  # one-wave teams of four chunks per lane
+    ("f32", 512, 1, (2, 3), 4, 2, 19),                   # float32: unit layout and one-piece layout side by side
+    ("f16", 4096, 1, (6, 3), 8, 2, 5),                   # whole-workgroup teams
+]
+
+
+@pytest.mark.parametrize("case", THREE_MIXES, ids=[f"{c[0]}-g{c[1]}-fw{'_'.join(map(str, c[3]))}-bw{c[4]}"
+                                                    for c in THREE_MIXES])
+def test_3bit_jobs_share_a_grid_with_other_widths(H, case):
+    """A whole time slot in one call (encode of step k, decode and grad_quant of step k-1,
+    grad_dequant of step k-2) over boundaries whose quantising jobs have 3 bits and other
+    widths at one team shape: they share a launch, the kernel variant with the 3-bit bodies."""
+    dtype, group, rnd, fws, bw, batch, gps = case
+    rng = np.random.default_rng(2000 + THREE_MIXES.index(case))
+    bs = [Boundary(H, rng, dtype, fb, group, rnd, bw, group, rnd, batch, group * gps, n_rows=2 * batch + 1,
+                   seed=300 + i) for i, fb in enumerate(fws)]
+    for step in range(4):
+        print("3-bit mix", case, "slot", step, flush=True)
+        jobs = []
+        if step >= 2:
+            jobs += [b.grad_dequant_job() for b in bs]       # message quantised in the slot before
+        if step >= 1:
+            jobs += [b.decode_job() for b in bs]             # message encoded in the slot before
+            jobs += [b.grad_quant_job() for b in bs]
+        jobs += [b.encode_job(step) for b in bs]
+        B.run_jobs(jobs)
+        for i, b in enumerate(bs):
+            b.verify(f"{case} boundary {i} slot {step}")
 
 
 def test_more_jobs_than_one_grid_holds_and_any_shape_jobs(H):
