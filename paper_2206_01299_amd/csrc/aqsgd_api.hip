@@ -87,6 +87,14 @@ std::atomic<int>& dequant_unroll_knob() {
     return v;
 }
 
+// Workgroups per launch that carries several jobs; 0 = the library's own choice (see
+// launch_budget).  For sweeps only: AQSGD_LAUNCH_BLOCKS in the environment.
+int64_t env_launch_blocks() { return env_int("AQSGD_LAUNCH_BLOCKS", 0); }
+std::atomic<int64_t>& launch_blocks_knob() {
+    static std::atomic<int64_t> v{env_launch_blocks()};
+    return v;
+}
+
 constexpr int64_t kMaxGridY = 65535;
 constexpr int kMaxTeamChunks = 4096;     // 1024 lanes x 4 chunks x 8 elements = 32768 elements
 
@@ -124,12 +132,15 @@ int team_shape_for(int cpg) {
     return kTeam1024x4;
 }
 
-int teams_per_block(int shape) {
+// Groups one step of a workgroup of the quantising kernel covers (its teams times the
+// groups each takes, groups_per_team).
+int groups_per_block_step(int shape) {
     switch (shape) {
-    case kTeam8x1: return kBlock / 8;
-    case kTeam16x1: return kBlock / 16;
-    case kTeam32x1: return kBlock / 32;
-    case kTeam64x1: case kTeam64x2: case kTeam64x3: case kTeam64x4: return kBlock / 64;
+    case kTeam8x1: return kBlock / 8 * groups_per_team(8, 1);
+    case kTeam16x1: return kBlock / 16 * groups_per_team(16, 1);
+    case kTeam32x1: return kBlock / 32 * groups_per_team(32, 1);
+    case kTeam64x1: return kBlock / 64 * groups_per_team(64, 1);
+    case kTeam64x2: case kTeam64x3: case kTeam64x4: return kBlock / 64;
     default: return 1;
     }
 }
@@ -206,6 +217,66 @@ DequantPlan plan_dequant(const aqsgd_desc* d, int64_t batch, int64_t n_per, cons
     return p;
 }
 
+// Workgroup budget of a launch led by quantising jobs of team shape `shape`.  A step of a
+// small team (one chunk per lane) is short next to what opens a workgroup (job lookup,
+// sample id, row addresses: dependent fetches), so a launch of many such workgroups keeps
+// much of the chip in that opening; such launches get about as many workgroups as are
+// resident at once (eight per compute unit) and each loops over several steps.  Measured
+// on the 2-bit G = 128 and the 3-bit G = 64 boundaries: whole step 7-8 % shorter in the
+// pipelined schedule, the launch on its own up to 7 % longer.  Launches of the wider
+// shapes (a step is four chunks per lane or a whole workgroup's row) lose from it and
+// keep one step per workgroup.
+int64_t launch_budget(int shape, int64_t knob) {
+    if (knob > 0) return knob;
+    switch (shape) {
+    case kTeam8x1: case kTeam16x1: case kTeam32x1: return 2048;
+    default: return int64_t{1} << 40;
+    }
+}
+
+// Workgroup numbers of a table whose jobs are all in: every job gets the grid its size
+// asks for (at most max_blocks), and when the launch as a whole would pass
+// `launch_blocks` workgroups the jobs share that budget in proportion to what they asked
+// for (the kernels loop over what is left).  quant_step / dequant_step: groups, chunks one
+// workgroup step covers.
+void number_blocks(JobTable& t, int64_t quant_step, int64_t dequant_step, int64_t max_blocks,
+                   int64_t launch_blocks) {
+    int64_t want[kMaxQuantJobs + kMaxDequantJobs];
+    int64_t total = 0;
+    for (int k = 0; k < t.n_quant; ++k) {
+        const LaunchGeom g = geometry(t.q[k].gps, quant_step, t.q[k].batch, max_blocks);
+        total += want[k] = static_cast<int64_t>(g.grid_x) * g.grid_y;
+    }
+    for (int k = 0; k < t.n_dequant; ++k) {
+        const LaunchGeom g = geometry(t.d[k].cps, dequant_step, t.d[k].batch, max_blocks);
+        total += want[kMaxQuantJobs + k] = static_cast<int64_t>(g.grid_x) * g.grid_y;
+    }
+    const bool shrink = total > launch_blocks;
+    auto share = [&](int64_t w) {
+        if (!shrink) return max_blocks;
+        const int64_t part = static_cast<int64_t>(static_cast<double>(launch_blocks) * static_cast<double>(w) /
+                                                  static_cast<double>(total));
+        return part < 1 ? int64_t{1} : (part < max_blocks ? part : max_blocks);
+    };
+    int64_t blocks = 0;
+    for (int k = 0; k < t.n_quant; ++k) {
+        QuantJob& a = t.q[k];
+        const LaunchGeom g = geometry(a.gps, quant_step, a.batch, share(want[k]));
+        a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
+        t.q_block0[k] = static_cast<uint32_t>(blocks);
+        blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
+    }
+    t.dequant_block0 = static_cast<uint32_t>(blocks);
+    for (int k = 0; k < t.n_dequant; ++k) {
+        DequantJob& a = t.d[k];
+        const LaunchGeom g = geometry(a.cps, dequant_step, a.batch, share(want[kMaxQuantJobs + k]));
+        a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
+        t.d_block0[k] = static_cast<uint32_t>(blocks);
+        blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
+    }
+    t.total_blocks = static_cast<uint32_t>(blocks);
+}
+
 // The launches of a set of independent messages: quantising jobs that share dtype,
 // rounding mode and team shape go into one grid, together with the dequantising
 // jobs of that dtype that are still waiting; dequantising jobs without such a host get a
@@ -218,15 +289,11 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
     std::vector<bool> q_done(qs.size(), false), d_done(ds.size(), false);
     hipError_t err = hipSuccess;
 
-    auto add_dequant = [&](JobTable& t, int dtype, int threads, int job_unroll, int64_t& blocks) {
+    const int64_t launch_blocks = launch_blocks_knob().load(std::memory_order_relaxed);
+    auto add_dequant = [&](JobTable& t, int dtype) {
         for (size_t k = 0; k < ds.size() && t.n_dequant < kMaxDequantJobs; ++k) {
             if (d_done[k] || !ds[k].flat || ds[k].dtype != dtype) continue;
-            DequantJob a = ds[k].job;
-            const LaunchGeom g = geometry(a.cps, static_cast<int64_t>(threads) * job_unroll, a.batch, max_blocks);
-            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
-            t.d_block0[t.n_dequant] = static_cast<uint32_t>(blocks);
-            blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
-            t.d[t.n_dequant++] = a;
+            t.d[t.n_dequant++] = ds[k].job;
             d_done[k] = true;
         }
     };
@@ -243,24 +310,19 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         }
         JobTable t;
         t.n_quant = t.n_dequant = 0;
-        int64_t blocks = 0;
         bool three = false;                              // a 3-bit job among them: the kernel variant that has those bodies
         for (size_t k = i; k < qs.size() && t.n_quant < kMaxQuantJobs; ++k) {
             const QuantPlan& c = qs[k];
             if (q_done[k] || c.shape != lead.shape || c.dtype != lead.dtype || c.rounding != lead.rounding)
                 continue;
             three = three || c.bits == 3;
-            QuantJob a = c.job;
-            const LaunchGeom g = geometry(a.gps, teams_per_block(c.shape), a.batch, max_blocks);
-            a.grid_x = g.grid_x; a.grid_y = g.grid_y; a.rcp_grid_x = 1.0f / static_cast<float>(g.grid_x);
-            t.q_block0[t.n_quant] = static_cast<uint32_t>(blocks);
-            blocks += static_cast<int64_t>(g.grid_x) * g.grid_y;
-            t.q[t.n_quant++] = a;
+            t.q[t.n_quant++] = c.job;
             q_done[k] = true;
         }
-        t.dequant_block0 = static_cast<uint32_t>(blocks);
-        add_dequant(t, lead.dtype, threads_of_shape(lead.shape), kHostedDequantUnroll, blocks);
-        t.total_blocks = static_cast<uint32_t>(blocks);
+        add_dequant(t, lead.dtype);
+        number_blocks(t, groups_per_block_step(lead.shape),
+                      static_cast<int64_t>(threads_of_shape(lead.shape)) * kHostedDequantUnroll, max_blocks,
+                      launch_budget(lead.shape, launch_blocks));
         err = launch_codec_jobs(lead.dtype, lead.rounding, lead.shape, three, t, stream);
     }
     for (size_t i = 0; i < ds.size() && err == hipSuccess; ++i) {
@@ -275,10 +337,8 @@ int launch_plans(std::vector<QuantPlan>& qs, std::vector<DequantPlan>& ds, hipSt
         }
         JobTable t;
         t.n_quant = t.n_dequant = 0;
-        t.dequant_block0 = 0;
-        int64_t blocks = 0;
-        add_dequant(t, ds[i].dtype, kBlock, unroll, blocks);
-        t.total_blocks = static_cast<uint32_t>(blocks);
+        add_dequant(t, ds[i].dtype);
+        number_blocks(t, 1, static_cast<int64_t>(kBlock) * unroll, max_blocks, launch_budget(-1, launch_blocks));
         err = launch_dequant_jobs(ds[i].dtype, unroll, t, stream);
     }
     return err == hipSuccess ? AQSGD_OK : AQSGD_ERR_LAUNCH;

@@ -116,6 +116,15 @@ __device__ __forceinline__ bool first_visit(const uint32_t* seen, int64_t row, u
 
 constexpr int kBlock = 256;
 
+// Groups a team of the quantising kernel takes per step.  A lane of a small team holds
+// one chunk of a group, so a workgroup step over one group per team would set up a
+// workgroup (job lookup, sample id, row addresses) for eight elements per lane and keep
+// two loads per lane in flight; such teams take four groups per step instead, all loads
+// first, which is the register budget of the four-chunks-per-lane shapes.
+__host__ __device__ constexpr int groups_per_team(int team, int cpl) {
+    return (team < kWave && cpl == 1) ? 2 : 1;
+}
+
 // ---------------------------------------------------------------------------
 // encode / grad_quant, team kernel.
 //
@@ -126,10 +135,10 @@ constexpr int kBlock = 256;
 // store the same bytes to the same place.  Only a team past the last group of
 // the sample (ragged last step) is switched off, as a whole.
 // ---------------------------------------------------------------------------
-template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF>
+template <int DT, int BITS, int ROUND, int TEAM, int CPL, bool HAS_BUF, int NG>
 __device__ __forceinline__ void quant_team_group(const QuantJob& a, const char* src_s, char* m_s,
                                                  uint8_t* codes_s, float* scales_s, int64_t src0,
-                                                 int64_t g, const uint32_t (&cc)[CPL],
+                                                 int64_t g0, int64_t gstride, const uint32_t (&cc)[CPL],
                                                  const uint32_t (&ua)[CPL], const uint32_t (&ub)[CPL],
                                                  int lane_in_team, float* wave_max) {
     constexpr bool kMultiWave = TEAM > kWave;
@@ -138,95 +147,113 @@ __device__ __forceinline__ void quant_team_group(const QuantJob& a, const char* 
     constexpr int kChunkBytes = kChunk * kEB;
     constexpr int kUnitBytes = kUnit * kEB;
     constexpr bool kUnits = UnitLayout<DT, BITS>::value;   // float32: a chunk is two separate 16-byte units
+    static_assert(NG == 1 || !kMultiWave, "several groups per step: teams inside a wavefront only");
 
-    // ---- issue every load of the group ------------------------------------------
-    const int64_t goff = g * a.group;                    // element offset within the sample
-    Raw<DT> ra[CPL], rm[CPL];
+    // The team takes NG groups per step, gstride apart: g0, g0 + gstride, ...
+    // ---- issue every load of the groups -----------------------------------------
+    int64_t goff[NG];                                    // element offsets within the sample
+    Raw<DT> ra[NG][CPL], rm[NG][CPL];
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        if constexpr (kUnits) {
-            ra[k] = load_raw_units(src_s + goff * kEB + ua[k] * kUnitBytes, src_s + goff * kEB + ub[k] * kUnitBytes);
-            if constexpr (HAS_BUF)
-                rm[k] = load_raw_units(m_s + goff * kEB + ua[k] * kUnitBytes, m_s + goff * kEB + ub[k] * kUnitBytes);
-            else rm[k] = zero_raw<DT>();
-        } else {
-            ra[k] = load_raw_at<DT>(src_s + goff * kEB + cc[k] * kChunkBytes);
-            if constexpr (HAS_BUF) rm[k] = load_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes);
-            else rm[k] = zero_raw<DT>();
+    for (int u = 0; u < NG; ++u) {
+        goff[u] = (g0 + u * gstride) * a.group;
+#pragma unroll
+        for (int k = 0; k < CPL; ++k) {
+            if constexpr (kUnits) {
+                ra[u][k] = load_raw_units(src_s + goff[u] * kEB + ua[k] * kUnitBytes,
+                                          src_s + goff[u] * kEB + ub[k] * kUnitBytes);
+                if constexpr (HAS_BUF)
+                    rm[u][k] = load_raw_units(m_s + goff[u] * kEB + ua[k] * kUnitBytes,
+                                              m_s + goff[u] * kEB + ub[k] * kUnitBytes);
+                else rm[u][k] = zero_raw<DT>();
+            } else {
+                ra[u][k] = load_raw_at<DT>(src_s + goff[u] * kEB + cc[k] * kChunkBytes);
+                if constexpr (HAS_BUF) rm[u][k] = load_raw_at<DT>(m_s + goff[u] * kEB + cc[k] * kChunkBytes);
+                else rm[u][k] = zero_raw<DT>();
+            }
         }
     }
-    // Keep all of the group's loads ahead of the first use: the scheduler would
-    // otherwise sink them next to their consumers and leave two or three in flight.
+    // Keep all of the loads ahead of the first use: the scheduler would otherwise
+    // sink them next to their consumers and leave two or three in flight.
     __builtin_amdgcn_sched_barrier(0);
 
     // ---- rounding offsets: they depend on the element index only, so the generator
     //      runs while the loads are in flight (second barrier: it stays up here) -------
-    float r[CPL][kChunk];
+    float r[NG][CPL][kChunk];
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
-            if constexpr (kUnits)
-                units_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + ua[k] * kUnit,
-                               static_cast<uint64_t>(src0 + goff) + ub[k] * kUnit, r[k]);
-            else
-                chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff) + cc[k] * kChunk, r[k]);
-        } else {
+    for (int u = 0; u < NG; ++u) {
 #pragma unroll
-            for (int e = 0; e < kChunk; ++e) r[k][e] = kNearestOffset32;
+        for (int k = 0; k < CPL; ++k) {
+            if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {
+                if constexpr (kUnits)
+                    units_uniforms(a.seed, static_cast<uint64_t>(src0 + goff[u]) + ua[k] * kUnit,
+                                   static_cast<uint64_t>(src0 + goff[u]) + ub[k] * kUnit, r[u][k]);
+                else
+                    chunk_uniforms(a.seed, static_cast<uint64_t>(src0 + goff[u]) + cc[k] * kChunk, r[u][k]);
+            } else {
+#pragma unroll
+                for (int e = 0; e < kChunk; ++e) r[u][k][e] = kNearestOffset32;
+            }
         }
     }
     if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) __builtin_amdgcn_sched_barrier(0);
 
-    // ---- delta and the group's max-abs --------------------------------------------
-    float d[CPL][kChunk];
-    float mx = 0.0f;
+    // ---- delta and each group's max-abs ---------------------------------------------
+    float d[NG][CPL][kChunk];
+    GroupScale sc[NG];
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        delta_chunk<DT>(ra[k], rm[k], d[k]);
+    for (int u = 0; u < NG; ++u) {
+        float mx = 0.0f;
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) mx = __builtin_fmaxf(mx, __builtin_fabsf(d[k][e]));
+        for (int k = 0; k < CPL; ++k) {
+            delta_chunk<DT>(ra[u][k], rm[u][k], d[u][k]);
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) mx = __builtin_fmaxf(mx, __builtin_fabsf(d[u][k][e]));
+        }
+        mx = team_max<(TEAM < kWave ? TEAM : kWave)>(mx);
+        if constexpr (kMultiWave) {                      // the whole workgroup is in here
+            __syncthreads();                             // earlier readers of wave_max are done
+            if (threadIdx.x % kWave == 0) wave_max[threadIdx.x / kWave] = mx;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < kThreads / kWave; ++w) mx = __builtin_fmaxf(mx, wave_max[w]);
+        }
+        sc[u] = make_scale<BITS>(mx);
     }
-    mx = team_max<(TEAM < kWave ? TEAM : kWave)>(mx);
-    if constexpr (kMultiWave) {                          // the whole workgroup is in here
-        __syncthreads();                                 // earlier readers of wave_max are done
-        if (threadIdx.x % kWave == 0) wave_max[threadIdx.x / kWave] = mx;
-        __syncthreads();
-#pragma unroll
-        for (int w = 0; w < kThreads / kWave; ++w) mx = __builtin_fmaxf(mx, wave_max[w]);
-    }
-    const GroupScale sc = make_scale<BITS>(mx);
 
     // ---- quantise, pack, update m ---------------------------------------------------
 #pragma unroll
-    for (int k = 0; k < CPL; ++k) {
-        float q[kChunk], dh[kChunk];
+    for (int u = 0; u < NG; ++u) {
 #pragma unroll
-        for (int e = 0; e < kChunk; ++e) {
-            q[e] = level_of<BITS, ROUND>(d[k][e], sc, r[k][e]);
-            dh[e] = value_of(q[e], sc);
-        }
-        uint8_t* group_codes = codes_s + goff / kChunk * BITS;
-        if constexpr (kUnits) {
-            const uint64_t w = pack_levels<BITS>(q);
-            store_unit_codes<BITS>(group_codes + ua[k] * (BITS / 2), low_unit_codes<BITS>(w));
-            store_unit_codes<BITS>(group_codes + ub[k] * (BITS / 2), high_unit_codes<BITS>(w));
+        for (int k = 0; k < CPL; ++k) {
+            float q[kChunk], dh[kChunk];
+#pragma unroll
+            for (int e = 0; e < kChunk; ++e) {
+                q[e] = level_of<BITS, ROUND>(d[u][k][e], sc[u], r[u][k][e]);
+                dh[e] = value_of(q[e], sc[u]);
+            }
+            uint8_t* group_codes = codes_s + goff[u] / kChunk * BITS;
+            if constexpr (kUnits) {
+                const uint64_t w = pack_levels<BITS>(q);
+                store_unit_codes<BITS>(group_codes + ua[k] * (BITS / 2), low_unit_codes<BITS>(w));
+                store_unit_codes<BITS>(group_codes + ub[k] * (BITS / 2), high_unit_codes<BITS>(w));
+                if constexpr (HAS_BUF)
+                    store_raw_units(m_s + goff[u] * kEB + ua[k] * kUnitBytes, m_s + goff[u] * kEB + ub[k] * kUnitBytes,
+                                    updated_chunk<DT>(rm[u][k], dh));
+                continue;
+            }
+            if (BITS == 3 && TEAM % 4 == 0 && a.cpg % 4 == 0) {
+                // whole quads of lanes are inside the group or past its end
+                const bool inside = k * TEAM + lane_in_team < a.cpg;
+                store_codes3_quad(group_codes + (cc[k] & ~3u) * 3, static_cast<uint32_t>(pack_levels<BITS>(q)),
+                                  lane_in_team & 3, inside);
+            } else {
+                store_codes_at<BITS>(group_codes + cc[k] * BITS, pack_levels<BITS>(q));
+            }
             if constexpr (HAS_BUF)
-                store_raw_units(m_s + goff * kEB + ua[k] * kUnitBytes, m_s + goff * kEB + ub[k] * kUnitBytes,
-                                updated_chunk<DT>(rm[k], dh));
-            continue;
+                store_raw_at<DT>(m_s + goff[u] * kEB + cc[k] * kChunkBytes, updated_chunk<DT>(rm[u][k], dh));
         }
-        if (BITS == 3 && TEAM % 4 == 0 && a.cpg % 4 == 0) {
-            // whole quads of lanes are inside the group or past its end
-            const bool inside = k * TEAM + lane_in_team < a.cpg;
-            store_codes3_quad(group_codes + (cc[k] & ~3u) * 3, static_cast<uint32_t>(pack_levels<BITS>(q)),
-                              lane_in_team & 3, inside);
-        } else {
-            store_codes_at<BITS>(group_codes + cc[k] * BITS, pack_levels<BITS>(q));
-        }
-        if constexpr (HAS_BUF)
-            store_raw_at<DT>(m_s + goff * kEB + cc[k] * kChunkBytes, updated_chunk<DT>(rm[k], dh));
+        if (lane_in_team == 0) scales_s[g0 + u * gstride] = sc[u].s_tx;
     }
-    if (lane_in_team == 0) scales_s[g] = sc.s_tx;
 }
 
 // First visit of a sample on the sender: the team's chunks of the group go from act
@@ -264,6 +291,8 @@ __device__ __forceinline__ void quant_team_body(const QuantJob& a, uint32_t bx, 
     constexpr bool kMultiWave = TEAM > kWave;
     constexpr int kThreads = TEAM > kWave ? TEAM : kBlock;
     constexpr int kTeamsPerBlock = kMultiWave ? 1 : kThreads / TEAM;
+    constexpr int kGroupsPerTeam = groups_per_team(TEAM, CPL);
+    constexpr int kGroupsPerStep = kTeamsPerBlock * kGroupsPerTeam;
     constexpr int kEB = ElemBytes<DT>::value;
 
     const int lane_in_team = threadIdx.x % TEAM;
@@ -306,18 +335,31 @@ __device__ __forceinline__ void quant_team_body(const QuantJob& a, uint32_t bx, 
             }
         }
 
-        for (int64_t gbase = static_cast<int64_t>(bx) * kTeamsPerBlock; gbase < a.gps;
-             gbase += static_cast<int64_t>(a.grid_x) * kTeamsPerBlock) {
-            const int64_t g = gbase + team;              // uniform over the team
-            if (g >= a.gps) continue;
-            if constexpr (HAS_BUF) {
-                if (fresh) {                             // uniform over the workgroup
-                    copy_team_group<DT, BITS, TEAM, CPL>(a, src_s, m_s, g, cc, ua, ub);
+        // One step of the workgroup: kGroupsPerStep consecutive groups, kGroupsPerTeam per team.
+        for (int64_t gbase = static_cast<int64_t>(bx) * kGroupsPerStep; gbase < a.gps;
+             gbase += static_cast<int64_t>(a.grid_x) * kGroupsPerStep) {
+            if constexpr (kGroupsPerTeam > 1) {
+                if (!fresh && gbase + kGroupsPerStep <= a.gps) {         // uniform over the workgroup
+                    quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF, kGroupsPerTeam>(
+                        a, src_s, m_s, codes_s, scales_s, src0, gbase + team, kTeamsPerBlock, cc, ua, ub,
+                        lane_in_team, wave_max);
                     continue;
                 }
             }
-            quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF>(a, src_s, m_s, codes_s, scales_s, src0, g,
-                                                                  cc, ua, ub, lane_in_team, wave_max);
+            // a sample's ragged last step, first visits, and the shapes with one group per team
+#pragma unroll 1
+            for (int u = 0; u < kGroupsPerTeam; ++u) {
+                const int64_t g = gbase + u * kTeamsPerBlock + team;     // uniform over the team
+                if (g >= a.gps) continue;
+                if constexpr (HAS_BUF) {
+                    if (fresh) {                         // uniform over the workgroup
+                        copy_team_group<DT, BITS, TEAM, CPL>(a, src_s, m_s, g, cc, ua, ub);
+                        continue;
+                    }
+                }
+                quant_team_group<DT, BITS, ROUND, TEAM, CPL, HAS_BUF, 1>(a, src_s, m_s, codes_s, scales_s, src0, g,
+                                                                         0, cc, ua, ub, lane_in_team, wave_max);
+            }
         }
     }
 }

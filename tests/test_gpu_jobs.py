@@ -197,6 +197,22 @@ def test_3bit_jobs_share_a_grid_with_other_widths(H, case):
             b.verify(f"{case} boundary {i} slot {step}")
 
 
+def test_a_time_slot_over_the_launch_budget_of_small_teams(H):
+    """Small-team launches get a bounded number of workgroups, shared by the jobs in
+    proportion to their sizes, and every workgroup loops over several steps: a slot of four
+    messages whose grids would ask for several times that budget, with a ragged last step."""
+    rng = np.random.default_rng(8)
+    b = Boundary(H, rng, "f16", 2, 128, 1, 4, 128, 1, 3, 128 * 20011, n_rows=4, seed=77)
+    for step in range(3):
+        print("over budget, slot", step, flush=True)
+        jobs = [b.grad_dequant_job()] if step >= 2 else []
+        if step >= 1:
+            jobs += [b.decode_job(), b.grad_quant_job()]
+        jobs.append(b.encode_job(step))
+        B.run_jobs(jobs)
+        b.verify(f"over budget slot {step}")
+
+
 def test_more_jobs_than_one_grid_holds_and_any_shape_jobs(H):
     rng = np.random.default_rng(6)
     same = [Boundary(H, rng, "f16", 4, 256, 0, 8, 256, 1, 2, 256 * 13, n_rows=5, seed=70 + i) for i in range(11)]
