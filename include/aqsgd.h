@@ -154,8 +154,8 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
  * reads what another writes, and no two touch the same row of the same m_buf; they run
  * concurrently, in no particular order.  Results are bit-identical to the single calls.
  * How jobs share launches: quantising jobs (ENCODE, GRAD_QUANT) with the same dtype,
- * rounding and group-size class (and either all 3-bit or none 3-bit) share one grid, and the dequantising jobs of that
- * dtype join it; dequantising jobs without such a host share a grid of their own; up to
+ * rounding and group-size class share one grid whatever their bit widths, and the
+ * dequantising jobs of that dtype join it; dequantising jobs without such a host share a grid of their own; up to
  * 8 + 8 jobs per grid, more are split; jobs whose group is not a multiple of 8 or larger
  * than 32768 run on their own.  The typical stage-side call (one ENCODE and one
  * GRAD_DEQUANT, or one DECODE and one GRAD_QUANT) is one launch.
@@ -356,7 +356,10 @@ int aqsgd_check_ids(const int64_t* sample_ids, int64_t batch, int64_t n_samples,
  * from the environment (AQSGD_MAX_BLOCKS, AQSGD_DEQUANT_UNROLL) or the built-in default.
  * The two settings are atomics, read once per call: a change made while another host
  * thread is inside a codec call applies to that thread's next call.  AQSGD_ERR_SHAPE for
- * values out of range.
+ * values out of range.  A third setting of the same kind has no setter and exists for
+ * measurements only: AQSGD_LAUNCH_BLOCKS in the environment (read once per process) bounds
+ * the workgroups of a whole launch, shared by its jobs in proportion to their sizes; unset,
+ * the library bounds only launches of small groups (fewer than 512 elements), at 2048.
  */
 int aqsgd_set_launch_shape(int64_t max_blocks, int32_t dequant_unroll);
 
