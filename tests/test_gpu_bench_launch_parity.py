@@ -3,8 +3,11 @@ boundary at full size (8192-sample buffers, float16 [4, 1024, 1600] micro-batche
 every stream's part of the steps recorded into a HIP graph of its own with bench.py's own
 enqueueing code, and the graphs replayed twice on their streams: the default (one launch
 per time slot of the two stages, micro-batches dealt over two streams), the per-stage
-launches, and the four single calls on four streams.  Every output of every step, and
-every visited row of both copies of m, must equal the oracle's after each replay."""
+launches, and the four single calls on four streams; and the default schedule on the
+2-bit stochastic GPT2 boundary and on the DeBERTa-shaped boundary (100,000-sample
+bfloat16 buffers), whose slot launches share a workgroup budget.  Every output of every
+step, and every visited row of both copies of m, must equal the oracle's after each
+replay."""
 import numpy as np
 import pytest
 import torch
@@ -15,14 +18,19 @@ from paper_2206_01299_amd import binding as B
 from paper_2206_01299_amd import workloads as W
 
 
-@pytest.mark.parametrize("schedule,n_streams", [("pipeline", 2), ("stage", 2), ("calls", 4), ("pipeline", 1)])
-def test_graph_at_full_size_matches_the_oracle(schedule, n_streams):
+CASES = [("gpt2_4bit", "pipeline", 2), ("gpt2_4bit", "stage", 2), ("gpt2_4bit", "calls", 4),
+         ("gpt2_4bit", "pipeline", 1), ("gpt2_2bit_stochastic", "pipeline", 2), ("deberta_3bit", "pipeline", 2)]
+
+
+@pytest.mark.parametrize("config,schedule,n_streams", CASES, ids=[f"{c}-{s}-{n}" for c, s, n in CASES])
+def test_graph_at_full_size_matches_the_oracle(config, schedule, n_streams):
     if not torch.cuda.is_available():
         pytest.fail("needs the MI355X")
     B.lib()
     import bench
     import gpu_harness as H
-    cfg = W.gpt2_4bit()
+    cfg = getattr(W, config)()
+    print("bench launches", config, schedule, n_streams, flush=True)
     steps = 8
     wl = bench.Workload(cfg, pool=steps)                 # m starts at zero: replay 1 = first visits
     streams = [torch.cuda.Stream() for _ in range(n_streams)]
@@ -45,9 +53,9 @@ def test_graph_at_full_size_matches_the_oracle(schedule, n_streams):
                 g.replay()
         torch.cuda.synchronize()
         for k in range(steps):
-            want = cpu.forward(acts[k], ids[k], 0)
+            want = cpu.forward(acts[k], ids[k], 0x5EED0000 + 2 * k)    # bench.py's key per message
             H.compare_call(f"replay {replay} step {k} fwd", cfg, (wl.codes[k], wl.scales[k], wl.out[k]), want)
-            wantb = cpu.backward(grads[k], 0)
+            wantb = cpu.backward(grads[k], 0x5EED0001 + 2 * k)
             H.compare_call(f"replay {replay} step {k} bwd", cfg, (wl.bcodes[k], wl.bscales[k], wl.gout[k]), wantb)
         order = torch.from_numpy(cpu.order).to(wl.dev)
         for name, dev_m, want_m in (("send", wl.m_send, cpu.m_send), ("recv", wl.m_recv, cpu.m_recv)):
