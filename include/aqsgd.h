@@ -144,8 +144,9 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
  * stage in the middle of a pipeline has two boundaries, and Appendix A.1's K machines
  * are K-1 independent instances.  A launch of a few tens of MB spends a good part of its
  * time filling and draining the GPU, so messages that are ready together should share a
- * grid.  Each job is exactly one of the four calls above, with the same arguments,
- * meaning, alignment and preconditions:
+ * grid.  Each job is exactly one of the four calls above (or one of the two first-visit
+ * variants of encode and decode), with the same arguments, meaning, alignment and
+ * preconditions:
  *   AQSGD_JOB_ENCODE        src = act,  sample_ids, m_buf (i/o), codes and scales (out)
  *   AQSGD_JOB_DECODE        codes and scales (in), sample_ids, m_buf (i/o), out
  *   AQSGD_JOB_GRAD_QUANT    src = grad, codes and scales (out)
@@ -163,7 +164,11 @@ int aqsgd_grad_dequant(const aqsgd_desc* desc, const uint8_t* codes, const float
  * AQSGD_ERR_SHAPE for an unknown kind or a negative count) nothing is enqueued.
  */
 typedef enum {
-    AQSGD_JOB_ENCODE = 0, AQSGD_JOB_DECODE = 1, AQSGD_JOB_GRAD_QUANT = 2, AQSGD_JOB_GRAD_DEQUANT = 3
+    AQSGD_JOB_ENCODE = 0, AQSGD_JOB_DECODE = 1, AQSGD_JOB_GRAD_QUANT = 2, AQSGD_JOB_GRAD_DEQUANT = 3,
+    /* the two calls of Algorithm 1 with its first-visit branch (declared further down),
+     * same arguments and rules as aqsgd_encode_seen / aqsgd_decode_seen: */
+    AQSGD_JOB_ENCODE_SEEN = 4,    /* ENCODE's pointers + seen (i/o), stamp, first (out)      */
+    AQSGD_JOB_DECODE_SEEN = 5     /* DECODE's pointers + full (in), seen (i/o), stamp        */
 } aqsgd_job_kind;
 
 typedef struct {
@@ -175,6 +180,11 @@ typedef struct {
     uint8_t* codes;               /* written by the quantising, read by the other jobs */
     float* scales;
     void* out;                    /* DECODE, GRAD_DEQUANT                             */
+    uint32_t* seen;               /* the *_SEEN kinds: one word per sample of m_buf   */
+    int32_t* first;               /* ENCODE_SEEN: [batch], 1 where the sample was new */
+    const void* full;             /* DECODE_SEEN: uncompressed rows of the new samples */
+    uint32_t stamp;               /* the *_SEEN kinds: this call's stamp, non-zero    */
+    uint32_t reserved;            /* 0                                                */
 } aqsgd_job;
 
 int aqsgd_run_jobs(const aqsgd_job* jobs, int32_t n_jobs, void* stream);

@@ -42,14 +42,16 @@ class Desc(ctypes.Structure):
                 ("rounding", ctypes.c_int32), ("rng_seed", ctypes.c_uint64)]
 
 
-JOB_ENCODE, JOB_DECODE, JOB_GRAD_QUANT, JOB_GRAD_DEQUANT = 0, 1, 2, 3
+JOB_ENCODE, JOB_DECODE, JOB_GRAD_QUANT, JOB_GRAD_DEQUANT, JOB_ENCODE_SEEN, JOB_DECODE_SEEN = 0, 1, 2, 3, 4, 5
 
 
 class Job(ctypes.Structure):
     """Mirror of ``aqsgd_job``."""
     _fields_ = [("kind", ctypes.c_int32), ("desc", Desc), ("src", ctypes.c_void_p),
                 ("sample_ids", ctypes.c_void_p), ("m_buf", ctypes.c_void_p), ("codes", ctypes.c_void_p),
-                ("scales", ctypes.c_void_p), ("out", ctypes.c_void_p)]
+                ("scales", ctypes.c_void_p), ("out", ctypes.c_void_p), ("seen", ctypes.c_void_p),
+                ("first", ctypes.c_void_p), ("full", ctypes.c_void_p), ("stamp", ctypes.c_uint32),
+                ("reserved", ctypes.c_uint32)]
 
 
 class AqsgdError(RuntimeError):
@@ -285,6 +287,25 @@ def grad_dequant_job(desc: Desc, codes, scales, out) -> Job:
     _check(desc, rows=[(out, "out")], codes=codes, scales=scales)
     return Job(JOB_GRAD_DEQUANT, _copy_desc(desc), None, None, None, _dev(codes, "codes"),
                _dev(scales, "scales"), _dev(out, "out"))
+
+
+def encode_seen_job(desc: Desc, act, sample_ids, m_buf, seen, stamp: int, first, codes, scales) -> Job:
+    """An ``aqsgd_encode_seen`` call as one job of :func:`run_jobs`."""
+    _check(desc, rows=[(act, "act")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales)
+    _want(seen, "seen", torch.int32, desc.n_samples, exact=True)
+    _want(first, "first", torch.int32, desc.batch, exact=True)
+    return Job(JOB_ENCODE_SEEN, _copy_desc(desc), _dev(act, "act"), _dev(sample_ids, "sample_ids"),
+               _dev(m_buf, "m_buf"), _dev(codes, "codes"), _dev(scales, "scales"), None,
+               _dev(seen, "seen"), _dev(first, "first"), None, stamp & 0xFFFFFFFF, 0)
+
+
+def decode_seen_job(desc: Desc, codes, scales, full, sample_ids, m_buf, seen, stamp: int, out) -> Job:
+    """An ``aqsgd_decode_seen`` call as one job of :func:`run_jobs`."""
+    _check(desc, rows=[(out, "out"), (full, "full")], ids=sample_ids, m_buf=m_buf, codes=codes, scales=scales)
+    _want(seen, "seen", torch.int32, desc.n_samples, exact=True)
+    return Job(JOB_DECODE_SEEN, _copy_desc(desc), None, _dev(sample_ids, "sample_ids"), _dev(m_buf, "m_buf"),
+               _dev(codes, "codes"), _dev(scales, "scales"), _dev(out, "out"),
+               _dev(seen, "seen"), None, _dev(full, "full"), stamp & 0xFFFFFFFF, 0)
 
 
 def run_jobs(jobs, stream=None) -> None:

@@ -608,6 +608,28 @@ int aqsgd_run_jobs(const aqsgd_job* jobs, int32_t n_jobs, void* stream) {
             rc = check_grad_dequant(d, j.codes, j.scales, j.out);
             if (rc == AQSGD_OK && d->batch > 0) ds.push_back(plan_grad_dequant(d, j.codes, j.scales, j.out));
             break;
+        case AQSGD_JOB_ENCODE_SEEN: {
+            rc = check_encode(d, j.src, j.sample_ids, j.m_buf, j.codes, j.scales);
+            if (rc == AQSGD_OK && j.stamp == 0) rc = AQSGD_ERR_SHAPE;
+            if (rc != AQSGD_OK || d->batch == 0) break;
+            if (!j.seen || !j.first) { rc = AQSGD_ERR_NULL; break; }
+            if (!aligned(j.first, 4) || !aligned(j.seen, 4)) { rc = AQSGD_ERR_ALIGN; break; }
+            SeenArgs sa;
+            sa.seen = j.seen; sa.first = j.first; sa.stamp = j.stamp;
+            qs.push_back(plan_quant(d, d->batch, d->n_per, j.src, j.sample_ids, j.m_buf, j.codes, j.scales, sa));
+            break;
+        }
+        case AQSGD_JOB_DECODE_SEEN: {
+            rc = check_decode(d, j.codes, j.scales, j.sample_ids, j.m_buf, j.out);
+            if (rc == AQSGD_OK && j.stamp == 0) rc = AQSGD_ERR_SHAPE;
+            if (rc != AQSGD_OK || d->batch == 0) break;
+            if (!j.seen || !j.full) { rc = AQSGD_ERR_NULL; break; }
+            if (!aligned(j.full, 16) || !aligned(j.seen, 4)) { rc = AQSGD_ERR_ALIGN; break; }
+            SeenArgs sa;
+            sa.seen = j.seen; sa.full = j.full; sa.stamp = j.stamp;
+            ds.push_back(plan_dequant(d, d->batch, d->n_per, j.codes, j.scales, j.sample_ids, j.m_buf, j.out, sa));
+            break;
+        }
         default:
             rc = AQSGD_ERR_SHAPE;
         }

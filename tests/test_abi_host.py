@@ -150,7 +150,7 @@ def test_binding_checks_tensor_types_and_sizes_against_the_descriptor(monkeypatc
 
 
 def test_job_layout_matches_header():
-    assert ctypes.sizeof(B.Job) == 8 + 48 + 6 * 8
+    assert ctypes.sizeof(B.Job) == 8 + 48 + 9 * 8 + 8
     assert B.Job.desc.offset == 8 and B.Job.src.offset == 56 and B.Job.out.offset == 96
 
 

@@ -24,7 +24,7 @@ def H():
     return gpu_harness
 
 
-def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed):
+def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed, as_jobs=False):
     import oracle
     d = H.dev()
     td = B.DTYPE_NAME[dtype]
@@ -49,11 +49,32 @@ def _replay(H, dtype, bits, group, n_per, n_rows, batch, steps, rounding, seed):
         scales = torch.full((B.scales_count(desc),), float(0x5A), dtype=torch.float32, device=d)
         first = torch.full((batch,), -7, dtype=torch.int32, device=d)
         out = W.to_torch(W.to_storage(np.full((batch, n_per), 9.0, dtype=np.float32), dtype), dtype, d)
-        B.encode_seen(desc, act, ids, m_s, seen_s, 1 + step, first, codes, scales)
+        if as_jobs:
+            # the calls as jobs of a stage's launch, next to a backward message of that stage
+            gdesc = B.make_desc(batch=batch, n_per=n_per, bits=8, group=group, dtype=dtype)
+            g_np = W.to_storage(1e-3 * rng.standard_normal((batch, n_per)).astype(np.float32), dtype)
+            grad = W.to_torch(g_np, dtype, d)
+            gcodes = torch.empty(B.codes_bytes(gdesc), dtype=torch.uint8, device=d)
+            gscales = torch.empty(B.scales_count(gdesc), dtype=torch.float32, device=d)
+            gout = torch.empty((batch, n_per), dtype=td, device=d)
+            B.run_jobs([B.grad_quant_job(gdesc, grad, gcodes, gscales),
+                        B.encode_seen_job(desc, act, ids, m_s, seen_s, 1 + step, first, codes, scales)])
+        else:
+            B.encode_seen(desc, act, ids, m_s, seen_s, 1 + step, first, codes, scales)
         # the receiver is handed the uncompressed rows of the first visits only
         full = torch.where(first.view(-1, 1) == 1, act.view(batch, n_per), torch.zeros_like(act.view(batch, n_per)))
-        B.decode_seen(desc, codes, scales, full.contiguous(), ids, m_r, seen_r, 77 + step, out)
+        full = full.contiguous()
+        if as_jobs:
+            B.run_jobs([B.decode_seen_job(desc, codes, scales, full, ids, m_r, seen_r, 77 + step, out),
+                        B.grad_dequant_job(gdesc, gcodes, gscales, gout)])
+        else:
+            B.decode_seen(desc, codes, scales, full, ids, m_r, seen_r, 77 + step, out)
         torch.cuda.synchronize()
+        if as_jobs:
+            wgc, wgs = oracle.grad_quant(g_np.reshape(-1), dtype=dtype, bits=8, group=group, rounding=0, seed=0)
+            wgo = oracle.grad_dequant(wgc, wgs, dtype=dtype, bits=8, group=group)
+            assert H.same_bytes(gcodes.cpu().numpy(), wgc) and H.same_bytes(gscales.cpu().numpy(), wgs)
+            assert H.same_bytes(W.from_torch(gout, dtype).reshape(-1), wgo.reshape(-1))
 
         wf, wc, ws = oracle.encode_seen(a_np, ids_np, om_s, oseen_s, dtype=dtype, bits=bits, group=group,
                                         rounding=rounding, seed=1000 + step, fill=0x5A)
@@ -87,6 +108,38 @@ def test_rows_that_are_not_whole_16_byte_units_and_odd_groups(H):
 def test_gpt2_shape_first_epoch_then_second(H):
     """The GPT2-1.5B per-call shape: an epoch of first visits, then the same samples again."""
     _replay(H, "f16", bits=4, group=1600, n_per=1024 * 1600, n_rows=8, batch=4, steps=4, rounding=0, seed=7)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+def test_first_visit_calls_as_jobs_of_a_stage_launch(H, dtype):
+    """aqsgd_run_jobs with the two first-visit kinds: each shares a launch with a backward
+    message of its stage, on streams that mix first and later visits."""
+    _replay(H, dtype, bits=4, group=256, n_per=2048, n_rows=40, batch=6, steps=10, rounding=0, seed=13,
+            as_jobs=True)
+    _replay(H, dtype, bits=3, group=64, n_per=1600, n_rows=24, batch=4, steps=8, rounding=1, seed=14,
+            as_jobs=True)
+
+
+def test_seen_jobs_reject_bad_arguments(H):
+    import ctypes
+    ok = B.make_desc(batch=2, n_per=1600, n_samples=4, bits=4, group=1600, dtype="f16")
+    p = 4096
+    enc = B.Job(B.JOB_ENCODE_SEEN, ok, p, p, p, p, p, None, p, p, None, 1, 0)
+    dec = B.Job(B.JOB_DECODE_SEEN, ok, None, p, p, p, p, p, p, None, p, 1, 0)
+    L = B.lib()
+    def run(job):
+        return L.aqsgd_run_jobs((B.Job * 1)(job), 1, None)
+    for field, job, want in (("seen", enc, -1), ("first", enc, -1), ("seen", dec, -1), ("full", dec, -1)):
+        keep = getattr(job, field)
+        setattr(job, field, None)
+        assert run(job) == want, field
+        setattr(job, field, keep)
+    enc.stamp = 0
+    dec.stamp = 0
+    assert run(enc) == -5 and run(dec) == -5
+    enc.stamp = 1
+    enc.first = 4098
+    assert run(enc) == -6
 
 
 def test_seen_entry_points_reject_bad_arguments(H):
