@@ -127,6 +127,10 @@ def parse_args():
                     help="secondary line: the timed region at 10, 20, 40, 80, 160 and 320 steps in one process "
                          "(whole step and forward messages alone), to show what the length of the region "
                          "does to the per-step figures")
+    ap.add_argument("--boundaries", type=int, default=1,
+                    help="secondary line, with --config stress: this many stage boundaries (2/4/8-bit "
+                         "forward messages mixed) worked on at the same time, every launch carrying the "
+                         "messages of all of them; each boundary has its own buffers (17 GB)")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run three plain 1 GiB device-to-device tensor copies (known traffic: "
                          "1 GiB read, 1 GiB written) so hardware byte counters can be scaled")
@@ -760,6 +764,97 @@ def torch_copy_us(torch, src_pool, dst_pool, reps):
     return a.elapsed_time(b) * 1e3 / reps
 
 
+class Boundaries:
+    """Several stage boundaries handled at the same time (Appendix A.1's K machines are K-1
+    independent instances of the two-machine scheme; a machine in the middle has two of
+    them): the same schedules as Workload's, every launch carrying the messages of all the
+    boundaries.  Has what timed_steps() uses of a Workload."""
+
+    LEGS = Workload.LEGS
+
+    def __init__(self, wls):
+        self.wls = wls
+        self.torch, self.B, self.evict = wls[0].torch, wls[0].B, wls[0].evict
+
+    def step(self, k, backward=True):
+        for w in self.wls:
+            w.step(k, backward)
+
+    def leg_bytes(self):
+        out = {}
+        for w in self.wls:
+            for l, v in w.leg_bytes().items():
+                out[l] = out.get(l, 0.0) + v
+        return out
+
+    def fused_chain(self, ks, schedule, backward=True):
+        B, n = self.B, len(ks)
+        assert schedule == "pipeline"
+        for t in range(n + (2 if backward else 1)):
+            jobs = []
+            for w in self.wls:                           # the slot of Workload.fused_chain, per boundary
+                if t < n:
+                    jobs.append(w.job("encode", ks[t]))
+                if 0 <= t - 1 < n:
+                    jobs.append(w.job("decode", ks[t - 1]))
+                    if backward:
+                        jobs.append(w.job("grad_quant", ks[t - 1]))
+                if backward and 0 <= t - 2 < n:
+                    jobs.append(w.job("grad_dequant", ks[t - 2]))
+            if jobs:
+                B.run_jobs(jobs)
+
+
+def boundaries_line(args):
+    """The stress configuration as it is written: several boundaries with forward messages of
+    2, 4 and 8 bits worked on concurrently.  One aqsgd_run_jobs call per time slot holds the
+    slot's messages of every boundary (the library packs them into launches of up to 8 + 8
+    jobs); micro-batches are dealt over two streams as in the default schedule."""
+    import torch
+    from paper_2206_01299_amd import workloads as W
+    n_b = args.boundaries
+    cfgs = [W.stress(W.STRESS_BITS[i % len(W.STRESS_BITS)], i) for i in range(n_b)]
+    pool = max(4, -(-1_250_000_000 // (cfgs[0].n * cfgs[0].elem_bytes * n_b)))
+    wls = []
+    for i, c in enumerate(cfgs):
+        w = Workload(c, pool, seed=1234 + i)
+        w.preseed_and_drift()
+        wls.append(w)
+    both = Boundaries(wls)
+    K, Wm = args.steps, args.warmup
+    for k in range(Wm):
+        both.step(k)
+    torch.cuda.synchronize()
+    n_streams = args.streams or 2
+    step_dev, step_wall = timed_steps(both, Wm, K, args.launch, n_streams, schedule="pipeline")
+    fwd_dev, fwd_wall = timed_steps(both, Wm, K, args.launch, n_streams, backward=False, schedule="pipeline")
+    lb = both.leg_bytes()
+    act_bytes = sum(c.n * c.elem_bytes for c in cfgs)
+    fwd_bytes, step_bytes = lb["encode"] + lb["decode"], sum(lb[l] for l in Workload.LEGS)
+    value = act_bytes / (fwd_dev / K) / 1e9
+    line = {
+        "metric": "encode+decode GB/s of activations, %d stress-shaped boundaries at the same time" % n_b,
+        "value": round(value, 2), "unit": "GB/s", "n_gpus": 1, "steps": K, "warmup": Wm,
+        "ms_per_step": round(step_dev / K * 1e3, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": "%d stage boundaries, each float32 activations [8,2048,4096], 256-sample m_buf x2, "
+                               "forward %s-bit per-row delta codec, backward 8-bit direct; a step is one "
+                               "micro-batch of every boundary" % (n_b, "/".join(str(c.fwd_bits) for c in cfgs)),
+                   "name": "stress_%d_boundaries" % n_b, "schedule": "pipeline", "streams": n_streams,
+                   "value_is": "activation bytes of one micro-batch of every boundary / time of their encodes "
+                               "and decodes (second timed run without the backward messages)"},
+        "roofline": None, "cpu_baseline": None,
+        "fwd_only": {"us_per_step": round(fwd_dev / K * 1e6, 2),
+                     "hbm_GBps": round(fwd_bytes / (fwd_dev / K) / 1e9, 1),
+                     "frac_of_hbm_peak": round(fwd_bytes / (fwd_dev / K) / 1e9 / HBM_PEAK_GBPS, 4)},
+        "whole_step": {"us": round(step_dev / K * 1e6, 2),
+                       "hbm_GBps": round(step_bytes / (step_dev / K) / 1e9, 1),
+                       "frac_of_hbm_peak": round(step_bytes / (step_dev / K) / 1e9 / HBM_PEAK_GBPS, 4),
+                       "algorithmic_bytes": step_bytes},
+    }
+    print(json.dumps(line))
+
+
 def first_visit_line(args, cfg, wl):
     """Algorithm 1's first-visit branch: one epoch in which every sample is new (the message
     is the activation itself, both stages store it as m), then the same calls again (every
@@ -960,6 +1055,12 @@ def main():
     cfg = {"gpt2_4bit": W.gpt2_4bit, "gpt2_2bit_stochastic": W.gpt2_2bit_stochastic,
            "deberta_3bit": W.deberta_3bit, "stress": W.stress}[args.config]()
     K, Wm = args.steps, args.warmup
+    if args.boundaries > 1:
+        if args.config != "stress" or args.boundaries > 8:
+            print("bench.py: --boundaries (2..8) goes with --config stress.", file=sys.stderr)
+            sys.exit(2)
+        boundaries_line(args)
+        return
     if args.pool <= 0:
         args.pool = max(4, -(-1_250_000_000 // (cfg.n * cfg.elem_bytes)))
     t_setup = time.perf_counter()
