@@ -729,6 +729,25 @@ def read_traffic():
     return vals or None
 
 
+def read_slot_traffic(config):
+    """The same for the slot launch of configurations 3, 4 and 5: read + written HBM bytes from
+    the committed counter summary of that configuration (None if there is none)."""
+    f = ROOT / "profiles" / "hbm_traffic_configs_3_4_5.md"
+    if not f.exists():
+        return None
+    rows = f.read_text().splitlines()
+    for i, line in enumerate(rows):
+        if line.startswith(f"## {config} "):
+            for data in rows[i + 1:i + 5]:
+                cols = data.split()
+                if len(cols) == 6:
+                    try:
+                        return (float(cols[0]) + float(cols[3])) * 1e6
+                    except ValueError:
+                        continue
+    return None
+
+
 def isolated_launches(torch, B, count, launch):
     """Average device duration (us) of `count` single launches made by launch(i), each
     stamped by the library's timed-launch hook on its own stream."""
@@ -1124,6 +1143,12 @@ def main():
                     "traffic": (traffic or {}).get(f"{dominant.split('(')[0]}_hbm_bytes_per_launch"),
                     "traffic_source": "stored rocprofv3 counter value (profiles/hbm_traffic_gpt2_fw4.txt), "
                                       "not measured in this run" if traffic else None}
+        if (traffic is None and dominant.startswith("slot_launch") and not args.m_bits and not args.bwd_keep):
+            slot = read_slot_traffic(args.config)        # configurations 3, 4, 5
+            if slot:
+                roofline["traffic"] = slot
+                roofline["traffic_source"] = ("stored rocprofv3 counter value "
+                                              "(profiles/hbm_traffic_configs_3_4_5.md), not measured in this run")
         pair_us = legs["encode"]["avg_us"] + legs["decode"]["avg_us"]
         pair_bytes = lb["encode"] + lb["decode"]
         extra["fwd_pair_isolated_launches"] = {"us": round(pair_us, 3),
