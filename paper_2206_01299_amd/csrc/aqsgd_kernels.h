@@ -128,8 +128,10 @@ __host__ __device__ constexpr int groups_per_team(int team, int cpl) {
 // ---------------------------------------------------------------------------
 // encode / grad_quant, team kernel.
 //
-// One step of a workgroup covers kTeamsPerBlock consecutive groups, one per
-// team.  Lanes past the end of a group do not branch around their loads: they
+// One step of a workgroup covers consecutive groups, groups_per_team() of them
+// per team (NG below; a team's groups lie kTeamsPerBlock apart, so that the
+// teams of a workgroup read consecutive groups with every load instruction).
+// Lanes past the end of a group do not branch around their loads: they
 // re-read the group's last chunk, whose values are already in the maximum, hold
 // a copy of its results (loaded by the same instruction as the original) and
 // store the same bytes to the same place.  Only a team past the last group of
