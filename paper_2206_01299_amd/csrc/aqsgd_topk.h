@@ -240,10 +240,10 @@ __device__ __forceinline__ float f32_of_bits16(uint32_t h) {
 // that byte cancelled by an exclusive-or a sharing entry is left below 256 and every other
 // entry at 256 or above, where min() caps it at the lane's spare counter (counters from
 // 256 on are never read).  Returns the digit that holds rank `need` and updates need / in_bin.
-template <int CPL, int LEVEL>
+template <int CPL, int LEVEL, bool TAIL>
 __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], const bool (&valid)[CPL],
-                                                  uint32_t prefix, int lane, uint32_t* bins, uint32_t& need,
-                                                  uint32_t& in_bin) {
+                                                  uint32_t tail_m2, bool tail_valid, uint32_t prefix, int lane,
+                                                  uint32_t* bins, uint32_t& need, uint32_t& in_bin) {
     const u32x4_t zero = {0u, 0u, 0u, 0u};
     *reinterpret_cast<u32x4_t*>(bins + 4 * lane) = zero;
     wave_lds_sync();
@@ -265,6 +265,12 @@ __device__ __forceinline__ uint32_t radix_level16(const uint32_t (&m)[CPL][4], c
                 }
             }
         }
+    if constexpr (TAIL) {                                // the lane's single entry of the last round
+        if (tail_valid) {
+            if constexpr (LEVEL == 1) atomicAdd(&bins[tail_m2 >> 8], 1u);
+            else atomicAdd(&bins[min(tail_m2 ^ (prefix << 8), spare)], 1u);
+        }
+    }
     wave_lds_sync();
     u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
     const uint32_t mine = c[0] + c[1] + c[2] + c[3];
@@ -306,8 +312,21 @@ __device__ __forceinline__ void load_group16(const TopkArgs& a, int64_t g, const
     for (int k = 0; k < CPL; ++k) raw[k] = load_raw_at<DT>(src + cc[k] * (kChunk * 2));
 }
 
-template <int DT, int CPL>
+// Entries of a 64-bit lane mask below this lane.
+__device__ __forceinline__ int lanes_set_below(uint64_t mask) {
+    return static_cast<int>(__builtin_amdgcn_mbcnt_hi(static_cast<uint32_t>(mask >> 32),
+                                                      __builtin_amdgcn_mbcnt_lo(static_cast<uint32_t>(mask), 0u)));
+}
+
+// TAIL: the group is CPL full rounds of chunks (one chunk per lane and round) followed by at
+// most eight more chunks, i.e. at most one entry per lane, which the lanes take as single
+// entries (`tail_raw`: the entry as stored; `tail_valid`: the lane has one) instead of
+// eight lanes taking a chunk each through one more round of whole-chunk work for everyone
+// - a 1600-entry group is three rounds and one such entry, not four rounds.  Ballots give
+// the tail's bitmap bytes and positions directly.
+template <int DT, int CPL, bool TAIL>
 __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g, const Raw<DT> (&raw)[CPL],
+                                                   uint32_t tail_raw, bool tail_valid,
                                                    const uint32_t (&cc)[CPL], const bool (&valid)[CPL], int lane,
                                                    TopkLds& lds) {
     const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
@@ -322,14 +341,19 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
             m2[k][i] = pk_add_u16(raw[k].v[i], raw[k].v[i]);
             top = pk_max_u16(top, m2[k][i]);
         }
+    uint32_t tail_m2 = 0;
+    if constexpr (TAIL) {
+        tail_m2 = tail_valid ? (tail_raw + tail_raw) & 0xffffu : 0u;
+        top = pk_max_u16(top, tail_m2);
+    }
     top = max(top & 0xffffu, top >> 16) >> 1;
     top = __float_as_uint(team_max<kWave>(__uint_as_float(top)));    // an integer maximum over the lanes
     const GroupScale sc = make_scale<kTopkBits>(f32_of_bits16<DT>(top));
 
     // ---- the keep-th largest magnitude: two levels, eight then seven bits ---------------------
     uint32_t need = static_cast<uint32_t>(a.keep), in_bin = 0;
-    const uint32_t hi8 = radix_level16<CPL, 1>(m2, valid, 0u, lane, lds.bins, need, in_bin);
-    const uint32_t lo7x2 = radix_level16<CPL, 0>(m2, valid, hi8, lane, lds.bins, need, in_bin);
+    const uint32_t hi8 = radix_level16<CPL, 1, TAIL>(m2, valid, tail_m2, tail_valid, 0u, lane, lds.bins, need, in_bin);
+    const uint32_t lo7x2 = radix_level16<CPL, 0, TAIL>(m2, valid, tail_m2, tail_valid, hi8, lane, lds.bins, need, in_bin);
     const uint32_t threshold = ((hi8 << 8) | lo7x2) >> 1;
     const int equal_kept = static_cast<int>(need), equal_total = static_cast<int>(in_bin);
     const uint32_t tt = threshold | (threshold << 16);
@@ -343,6 +367,9 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
         for (int i = 0; i < 4; ++i) d[i] = pk_sub_u16(raw[k].v[i] & 0x7fff7fffu, tt);   // sign set: below the threshold
         geb[k] = valid[k] ? ~sign_mask16(d) & 0xffu : 0u;
     }
+    const uint32_t tail_mag = tail_raw & 0x7fffu;
+    const bool tail_ge = TAIL && tail_valid && tail_mag >= threshold;
+    bool tail_keep = tail_ge;
     uint32_t keepb[CPL];
     if (equal_kept == equal_total) {                     // no choice to make among equals (wave-uniform)
 #pragma unroll
@@ -377,6 +404,10 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
             keepb[k] = kb;
             left = max(left - static_cast<int>(ties_total[k]), 0);
         }
+        if constexpr (TAIL) {                            // the tail's entries come last in entry order
+            const bool tail_eq = tail_ge && tail_mag == threshold;
+            tail_keep = tail_ge && (!tail_eq || lanes_set_below(__ballot(tail_eq)) < left);
+        }
     }
 
     // ---- the kept entries, as stored, in entry order into LDS ----------------------------------
@@ -404,6 +435,13 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
         }
         if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb[k]);
         row_start += kept_total[k];
+    }
+    if constexpr (TAIL) {
+        const uint64_t km = __ballot(tail_keep);         // bit l: lane l's entry, which is entry 64 * 8 * CPL + l
+        if (tail_keep) lds.stage16[row_start + static_cast<uint32_t>(lanes_set_below(km))] = static_cast<uint16_t>(tail_raw);
+        const int tail_chunks = a.cpg - CPL * kWave;
+        if (lane < tail_chunks)
+            a.bitmap[e0 / kChunk + CPL * kWave + lane] = static_cast<uint8_t>(km >> (8 * lane));
     }
     wave_lds_sync();
 
@@ -630,11 +668,43 @@ void topk_kernel(const TopkArgs a) {
         // round of waves that all start by waiting for memory, and whatever does not depend
         // on the data (lane constants, clearing counters) is then worked off during that wait.
         if (g >= a.n_groups) return;
+        if constexpr (CPL >= 2) {
+            // a last round of at most eight chunks is taken as one entry per lane (see above)
+            constexpr int kRounds = CPL - 1;
+            const int tail_chunks = a.cpg - kRounds * kWave;
+            if (tail_chunks >= 1 && tail_chunks <= 8) {              // uniform over the launch
+                uint32_t rc[kRounds];
+                bool all[kRounds];
+#pragma unroll
+                for (int k = 0; k < kRounds; ++k) {
+                    rc[k] = static_cast<uint32_t>(k * kWave + lane);
+                    all[k] = true;
+                }
+                const bool tail_valid = lane < kChunk * tail_chunks;
+                const int64_t tail_at = 2 * (kRounds * kWave * kChunk + min(lane, kChunk * tail_chunks - 1));
+                auto tail_of = [&](int64_t group) {
+                    return static_cast<uint32_t>(*reinterpret_cast<const uint16_t*>(
+                        static_cast<const char*>(a.grad) + group * a.group * 2 + tail_at));
+                };
+                Raw<DT> raw[kRounds];
+                load_group16<DT, kRounds>(a, g, rc, raw);
+                uint32_t tail_raw = tail_of(g);
+                __builtin_amdgcn_sched_barrier(0);
+                for (;;) {
+                    topk_quant_group16<DT, kRounds, true>(a, g, raw, tail_raw, tail_valid, rc, all, lane, lds_all[wave]);
+                    g += stride;
+                    if (g >= a.n_groups) break;
+                    load_group16<DT, kRounds>(a, g, rc, raw);
+                    tail_raw = tail_of(g);
+                }
+                return;
+            }
+        }
         Raw<DT> raw[CPL];
         load_group16<DT, CPL>(a, g, cc, raw);
         __builtin_amdgcn_sched_barrier(0);
         for (;;) {
-            topk_quant_group16<DT, CPL>(a, g, raw, cc, valid, lane, lds_all[wave]);
+            topk_quant_group16<DT, CPL, false>(a, g, raw, 0u, false, cc, valid, lane, lds_all[wave]);
             g += stride;
             if (g >= a.n_groups) break;
             load_group16<DT, CPL>(a, g, cc, raw);
