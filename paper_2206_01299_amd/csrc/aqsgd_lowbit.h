@@ -75,6 +75,49 @@ __device__ __forceinline__ void stored_values(uint64_t mw, const GroupScale& msc
     for (int e = 0; e < kChunk; ++e) m[e] = value_of(q[e], msc);
 }
 
+// ---------------------------------------------------------------------------
+// A last round of at most eight chunks taken as one element per lane.  A 1600-element
+// group is three rounds of one chunk per lane and 64 more elements; with whole chunks
+// those 64 cost every lane a fourth round of eight elements' arithmetic, and this kernel
+// is bound by arithmetic.  b-bit levels of eight neighbouring lanes make one chunk's b
+// bytes: they meet in the first of the eight lanes through three row shifts.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ uint32_t dpp_from_higher_lane(uint32_t v) {
+    // lane l reads lane l + n of its row of 16 (row_shl:n); lanes without a source read zero
+    return static_cast<uint32_t>(__builtin_amdgcn_update_dpp(0, static_cast<int>(v), CTRL, 0xf, 0xf, true));
+}
+
+constexpr bool tail_bits_ok(int b) { return b == 2 || b == 4 || b == 8; }
+
+// Every lane calls it (the shifts read the neighbours); `level` must be 0 in lanes without
+// an element.  base: the tail's first byte; the tail has tail_entries (a multiple of 8) elements.
+template <int B>
+__device__ __forceinline__ void store_tail_levels(uint8_t* base, uint32_t level, int lane, int tail_entries) {
+    static_assert(tail_bits_ok(B), "single-element tails: 2, 4 or 8 bits");
+    if constexpr (B == 8) {
+        if (lane < tail_entries) base[lane] = static_cast<uint8_t>(level);
+    } else {
+        uint32_t x = level;
+        x |= dpp_from_higher_lane<0x101>(x) << B;
+        x |= dpp_from_higher_lane<0x102>(x) << (2 * B);
+        x |= dpp_from_higher_lane<0x104>(x) << (4 * B);
+        if (lane % 8 == 0 && lane < tail_entries) {
+            if constexpr (B == 4) *reinterpret_cast<uint32_t*>(base + lane / 8 * 4) = x;
+            else *reinterpret_cast<uint16_t*>(base + lane / 8 * 2) = static_cast<uint16_t>(x);
+        }
+    }
+}
+
+// The level of tail element l (l inside the tail).
+template <int B>
+__device__ __forceinline__ uint32_t load_tail_level(const uint8_t* base, int l) {
+    static_assert(tail_bits_ok(B), "single-element tails: 2, 4 or 8 bits");
+    if constexpr (B == 8) return base[l];
+    else if constexpr (B == 4) return (static_cast<uint32_t>(base[l / 2]) >> (4 * (l & 1))) & 15u;
+    else return (static_cast<uint32_t>(base[l / 4]) >> (2 * (l & 3))) & 3u;
+}
+
 // One group.  The kernel is bound by vector arithmetic, not by memory (two quantisers and
 // a dequantiser per element), and registers decide how many waves a SIMD holds, so what is
 // live across the two reductions is chosen by what is cheapest to form again.  Sender with
@@ -84,12 +127,16 @@ __device__ __forceinline__ void stored_values(uint64_t mw, const GroupScale& msc
 // activations: d stays across the first reduction and m^ is formed again from the stored
 // levels when v is built.  Keeping d, m^ and v live all at once would cost a wave of
 // occupancy per SIMD and with it the chance to hold a whole launch on the chip at a time.
-template <int DT, int BITS, int MBITS, int ROUND, int TEAM, int CPL, bool SENDER>
+// TAIL (one-wave teams, 16-bit activations, nearest rounding): the group is CPL whole rounds
+// and `tail_entries` more elements, one per lane (see above).
+template <int DT, int BITS, int MBITS, int ROUND, int TEAM, int CPL, bool SENDER, bool TAIL = false>
 __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const char* act_s, char* out_s,
                                                   uint8_t* mcodes_s, float* mscales_s, uint8_t* codes_s,
                                                   float* scales_s, int64_t src0, int64_t g,
                                                   const uint32_t (&cc)[CPL], int lane_in_team,
-                                                  float* wave_max) {
+                                                  float* wave_max, int tail_entries = 0) {
+    static_assert(!TAIL || (TEAM == kWave && ElemBytes<DT>::value == 2 && ROUND == AQSGD_ROUND_NEAREST),
+                  "single-element tails: one-wave teams, 16-bit activations, nearest rounding");
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
     const int64_t goff = g * a.group;                    // element offset within the sample
@@ -110,9 +157,23 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
         if constexpr (SENDER) ra[k] = load_raw_at<DT>(act_s + goff * kEB + cc[k] * kChunkBytes);
         else cw[k] = load_codes_at<BITS>(c_group + cc[k] * static_cast<uint32_t>(BITS));
     }
+    // the tail: element CPL * 64 * 8 + lane of the group (a lane past the end repeats the last one)
+    [[maybe_unused]] const bool tail_valid = TAIL && lane_in_team < tail_entries;
+    [[maybe_unused]] const int tail_l = min(lane_in_team, tail_entries - 1);
+    [[maybe_unused]] const int64_t tail_e = goff + CPL * kWave * kChunk + tail_l;
+    [[maybe_unused]] uint8_t* const m_tail = m_group + CPL * kWave * MBITS;
+    [[maybe_unused]] uint8_t* const c_tail = c_group + CPL * kWave * BITS;
+    [[maybe_unused]] uint32_t tail_m = 0, tail_c = 0;
+    [[maybe_unused]] float tail_a = 0.0f, tail_v = 0.0f;
+    if constexpr (TAIL) {
+        tail_m = load_tail_level<MBITS>(m_tail, tail_l);
+        if constexpr (SENDER) tail_a = load_elem<DT>(act_s, tail_e);
+        else tail_c = load_tail_level<BITS>(c_tail, tail_l);
+    }
     __builtin_amdgcn_sched_barrier(0);
 
     const GroupScale msc = scale_from_wire<MBITS>(m_scale);      // m^ = Q_z^-1(stored)
+    if constexpr (TAIL) tail_v = value_of(static_cast<float>(tail_m), msc);     // m^ of the tail element
     float v[CPL][kChunk];                                        // m^ + Delta m
     float mx2 = 0.0f;                                            // max |v| for the storage scale
 
@@ -128,8 +189,19 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
 #pragma unroll
             for (int e = 0; e < kChunk; ++e) mx = __builtin_fmaxf(mx, __builtin_fabsf(d[e]));
         }
+        [[maybe_unused]] float tail_d = 0.0f;
+        if constexpr (TAIL) {
+            tail_d = tail_a - tail_v;
+            mx = __builtin_fmaxf(mx, tail_valid ? __builtin_fabsf(tail_d) : 0.0f);
+        }
         mx = team_max_all<TEAM, 0>(mx, wave_max);
         const GroupScale sc = make_scale<BITS>(mx);
+        if constexpr (TAIL) {
+            const float q = level_of<BITS, ROUND>(tail_d, sc, kNearestOffset32);
+            tail_v = tail_v + value_of(q, sc);
+            mx2 = __builtin_fmaxf(mx2, tail_valid ? __builtin_fabsf(tail_v) : 0.0f);
+            store_tail_levels<BITS>(c_tail, tail_valid ? static_cast<uint32_t>(q) : 0u, lane_in_team, tail_entries);
+        }
 #pragma unroll
         for (int k = 0; k < CPL; ++k) forget(ra[k]);     // d is formed again below, not kept
 #pragma unroll
@@ -194,6 +266,10 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
         if (lane_in_team == 0) scales_s[g] = sc.s_tx;
     } else {
         const GroupScale wsc = scale_from_wire<BITS>(wire_scale);
+        if constexpr (TAIL) {
+            tail_v = tail_v + value_of(static_cast<float>(tail_c), wsc);
+            mx2 = __builtin_fmaxf(mx2, tail_valid ? __builtin_fabsf(tail_v) : 0.0f);
+        }
 #pragma unroll
         for (int k = 0; k < CPL; ++k) {
             float m[kChunk], q[kChunk];
@@ -219,6 +295,13 @@ __device__ __forceinline__ void lowbit_team_group(const LowbitArgs& a, const cha
         store_codes_at<MBITS>(m_group + cc[k] * static_cast<uint32_t>(MBITS), pack_levels<MBITS>(q2));
         if constexpr (!SENDER) store_raw_at<DT>(out_s + goff * kEB + cc[k] * kChunkBytes, pack_raw<DT>(v[k]));
     }
+    if constexpr (TAIL) {
+        const float q2 = level_of<MBITS, AQSGD_ROUND_NEAREST>(tail_v, ssc, kNearestOffset32);
+        store_tail_levels<MBITS>(m_tail, tail_valid ? static_cast<uint32_t>(q2) : 0u, lane_in_team, tail_entries);
+        if constexpr (!SENDER) {
+            if (tail_valid) store_elem<DT>(out_s, tail_e, tail_v);
+        }
+    }
     if (lane_in_team == 0) mscales_s[g] = ssc.s_tx;
 }
 
@@ -227,7 +310,9 @@ enum LowbitMode { kLbReceiver = 0, kLbSenderNearest = 1, kLbSenderStochastic = 2
 
 // Four waves per SIMD hold a whole GPT2-sized launch (one wave per row) on the chip at
 // once; the hint makes the register allocator aim for that.
-template <int DT, int BITS, int MBITS, int TEAM, int CPL, int MODE>
+// TAILK: the launch's groups end in a last round of at most eight chunks, which is taken as one
+// element per lane (the host picks this variant; see lowbit_tail_chunks).
+template <int DT, int BITS, int MBITS, int TEAM, int CPL, int MODE, bool TAILK = false>
 __global__ __launch_bounds__((TEAM > kWave ? TEAM : kBlock)) __attribute__((amdgpu_waves_per_eu(4)))
 void lowbit_team_kernel(const LowbitArgs a) {
     constexpr bool SENDER = MODE != kLbReceiver;
@@ -257,6 +342,22 @@ void lowbit_team_kernel(const LowbitArgs a) {
         uint8_t* codes_s = a.codes + src0 / kChunk * BITS;
         float* scales_s = a.scales + static_cast<int64_t>(i) * a.gps;
 
+        if constexpr (TAILK) {
+            constexpr int kRounds = CPL - 1;
+            const int tail_chunks = a.cpg - kRounds * kWave;         // 1..8: checked by the host
+            uint32_t rc[kRounds];
+#pragma unroll
+            for (int k = 0; k < kRounds; ++k) rc[k] = static_cast<uint32_t>(k * kWave + lane_in_team);
+            for (int64_t gbase = static_cast<int64_t>(blockIdx.x) * kTeamsPerBlock; gbase < a.gps;
+                 gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
+                const int64_t g = gbase + team;
+                if (g < a.gps)
+                    lowbit_team_group<DT, BITS, MBITS, ROUND, TEAM, kRounds, SENDER, true>(
+                        a, act_s, out_s, mcodes_s, mscales_s, codes_s, scales_s, src0, g, rc, lane_in_team,
+                        wave_max, kChunk * tail_chunks);
+            }
+            continue;
+        }
         for (int64_t gbase = static_cast<int64_t>(blockIdx.x) * kTeamsPerBlock; gbase < a.gps;
              gbase += static_cast<int64_t>(gridDim.x) * kTeamsPerBlock) {
             const int64_t g = gbase + team;
@@ -280,6 +381,18 @@ hipError_t launch_lowbit(int dtype, int bits, int m_bits, int shape, bool sender
 template <int DT> hipError_t launch_lowbit_dt(int bits, int m_bits, int shape, bool sender, LaunchGeom g,
                                               const LowbitArgs& a, hipStream_t stream);
 
+// The single-element-tail variant exists for 16-bit activations, wire levels of 2, 4 or 8 bits
+// and everything but the stochastic sender; a launch takes it when its groups are cpl - 1 whole
+// rounds of a wavefront's chunks plus one to eight more chunks.
+template <int DT, int BITS, int MODE>
+constexpr bool lowbit_tail_variant() {
+    return ElemBytes<DT>::value == 2 && tail_bits_ok(BITS) && MODE != kLbSenderStochastic;
+}
+inline bool lowbit_tail_chunks(int cpg, int cpl) {
+    const int t = cpg - (cpl - 1) * kWave;
+    return t >= 1 && t <= 8;
+}
+
 // ---- launch table (instantiated per dtype in aqsgd_lowbit_<dtype>.hip) ----------------
 template <int DT, int BITS, int MBITS, int MODE>
 static hipError_t launch_lb_shape(int shape, LaunchGeom g, const LowbitArgs& a, hipStream_t s) {
@@ -289,8 +402,18 @@ static hipError_t launch_lb_shape(int shape, LaunchGeom g, const LowbitArgs& a, 
     case kLb16x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 16, 1, MODE>, grid, dim3(kBlock), s, a);
     case kLb32x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 32, 1, MODE>, grid, dim3(kBlock), s, a);
     case kLb64x1:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 1, MODE>, grid, dim3(kBlock), s, a);
-    case kLb64x2:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE>, grid, dim3(kBlock), s, a);
-    case kLb64x4:   return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x2:
+        if constexpr (lowbit_tail_variant<DT, BITS, MODE>()) {
+            if (lowbit_tail_chunks(a.cpg, 2))
+                return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE, true>, grid, dim3(kBlock), s, a);
+        }
+        return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x4:
+        if constexpr (lowbit_tail_variant<DT, BITS, MODE>()) {
+            if (lowbit_tail_chunks(a.cpg, 4))
+                return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, MODE, true>, grid, dim3(kBlock), s, a);
+        }
+        return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 4, MODE>, grid, dim3(kBlock), s, a);
     case kLb256x2:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 2, MODE>, grid, dim3(256), s, a);
     case kLb256x4:  return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 256, 4, MODE>, grid, dim3(256), s, a);
     case kLb1024x2: return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 1024, 2, MODE>, grid, dim3(1024), s, a);

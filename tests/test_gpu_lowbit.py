@@ -95,10 +95,12 @@ def _cfg(dtype, bits, group, rounding, gps, batch=3, n_samples=7):
 @pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
 @pytest.mark.parametrize("m_bits", [2, 8])
 def test_lowbit_sweep(H, dtype, m_bits):
-    """Every team shape of the low-precision-storage kernels, ragged tails included."""
-    for group in [8, 24, 64, 128, 200, 520, 1000, 1600, 2048, 4096, 8200, 16384]:
+    """Every team shape of the low-precision-storage kernels, ragged tails included (520, 576,
+    1560 and 1600: groups whose last round of chunks is taken as single elements per lane)."""
+    for group in [8, 24, 64, 128, 200, 520, 576, 1000, 1560, 1600, 2048, 4096, 8200, 16384]:
         gps = 37 if group <= 2048 else 5
-        for bits, rounding in [(4, W.NEAREST), (2, W.STOCHASTIC), (3, W.NEAREST), (6, W.STOCHASTIC), (8, W.NEAREST)]:
+        for bits, rounding in [(4, W.NEAREST), (2, W.STOCHASTIC), (3, W.NEAREST), (6, W.STOCHASTIC), (8, W.NEAREST),
+                               (2, W.NEAREST)]:
             if group > 2048 and bits not in (4, 2):
                 continue
             print(f"lowbit {dtype} m{m_bits} b{bits} G{group} r{rounding}", flush=True)
