@@ -456,6 +456,7 @@ int lowbit_shape_for(int cpg) {
     if (cpg <= 32) return kLb32x1;
     if (cpg <= 64) return kLb64x1;
     if (cpg <= 128) return kLb64x2;
+    if (cpg <= 192) return kLb64x3;
     if (cpg <= 256) return kLb64x4;
     if (cpg <= 512) return kLb256x2;
     if (cpg <= 1024) return kLb256x4;
@@ -467,7 +468,7 @@ int lowbit_teams_per_block(int shape) {
     case kLb8x1: return kBlock / 8;
     case kLb16x1: return kBlock / 16;
     case kLb32x1: return kBlock / 32;
-    case kLb64x1: case kLb64x2: case kLb64x4: return kBlock / 64;
+    case kLb64x1: case kLb64x2: case kLb64x3: case kLb64x4: return kBlock / 64;
     default: return 1;
     }
 }
@@ -513,7 +514,7 @@ int run_topk(const aqsgd_desc* d, int32_t keep, bool sender, const void* grad, v
     a.n_groups = d->batch * (d->n_per / d->group);
     a.group = d->group; a.cpg = d->group / kChunk; a.keep = keep;
     a.stochastic = d->rounding == AQSGD_ROUND_STOCHASTIC; a.seed = d->rng_seed;
-    const int cpl = a.cpg <= kWave ? 1 : (a.cpg <= 2 * kWave ? 2 : 4);
+    const int cpl = a.cpg <= kWave ? 1 : (a.cpg <= 2 * kWave ? 2 : (a.cpg <= 3 * kWave ? 3 : 4));
     const LaunchGeom g = geometry(a.n_groups, kTopkBlock / kWave, 1,
                                   max_blocks_knob().load(std::memory_order_relaxed));
     const hipError_t err = launch_topk(d->dtype, cpl, sender, g.grid_x, a, stream);

@@ -372,7 +372,7 @@ void lowbit_team_kernel(const LowbitArgs a) {
 // Team shapes of the low-precision-storage kernels (more live registers per
 // element than the plain codec, so the widest shapes stop at two chunks per lane).
 enum LowbitShape {
-    kLb8x1 = 0, kLb16x1, kLb32x1, kLb64x1, kLb64x2, kLb64x4, kLb256x2, kLb256x4, kLb1024x2, kNumLowbitShapes
+    kLb8x1 = 0, kLb16x1, kLb32x1, kLb64x1, kLb64x2, kLb64x3, kLb64x4, kLb256x2, kLb256x4, kLb1024x2, kNumLowbitShapes
 };
 constexpr int kMaxLowbitChunks = 2048;
 
@@ -408,6 +408,12 @@ static hipError_t launch_lb_shape(int shape, LaunchGeom g, const LowbitArgs& a, 
                 return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE, true>, grid, dim3(kBlock), s, a);
         }
         return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 2, MODE>, grid, dim3(kBlock), s, a);
+    case kLb64x3:
+        if constexpr (lowbit_tail_variant<DT, BITS, MODE>()) {
+            if (lowbit_tail_chunks(a.cpg, 3))
+                return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 3, MODE, true>, grid, dim3(kBlock), s, a);
+        }
+        return launch_kernel(lowbit_team_kernel<DT, BITS, MBITS, 64, 3, MODE>, grid, dim3(kBlock), s, a);
     case kLb64x4:
         if constexpr (lowbit_tail_variant<DT, BITS, MODE>()) {
             if (lowbit_tail_chunks(a.cpg, 4))

@@ -718,7 +718,7 @@ void topk_kernel(const TopkArgs a) {
     }
 }
 
-// chunks per lane: 1, 2 or 4 (groups of up to 512, 1024, 2048 entries)
+// chunks per lane: 1, 2, 3 or 4 (groups of up to 512, 1024, 1536, 2048 entries)
 hipError_t launch_topk(int dtype, int cpl, bool sender, unsigned blocks, const TopkArgs& a, hipStream_t stream);
 
 }  // namespace aqsgd

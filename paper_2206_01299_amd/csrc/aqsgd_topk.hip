@@ -9,6 +9,7 @@ static hipError_t launch_topk_cpl(int cpl, unsigned blocks, const TopkArgs& a, h
     switch (cpl) {
     case 1: return launch_kernel(topk_kernel<DT, 1, MODE>, dim3(blocks), dim3(kTopkBlock), s, a);
     case 2: return launch_kernel(topk_kernel<DT, 2, MODE>, dim3(blocks), dim3(kTopkBlock), s, a);
+    case 3: return launch_kernel(topk_kernel<DT, 3, MODE>, dim3(blocks), dim3(kTopkBlock), s, a);
     case 4: return launch_kernel(topk_kernel<DT, 4, MODE>, dim3(blocks), dim3(kTopkBlock), s, a);
     default: return hipErrorInvalidValue;
     }

@@ -97,7 +97,7 @@ def _cfg(dtype, bits, group, rounding, gps, batch=3, n_samples=7):
 def test_lowbit_sweep(H, dtype, m_bits):
     """Every team shape of the low-precision-storage kernels, ragged tails included (520, 576,
     1560 and 1600: groups whose last round of chunks is taken as single elements per lane)."""
-    for group in [8, 24, 64, 128, 200, 520, 576, 1000, 1560, 1600, 2048, 4096, 8200, 16384]:
+    for group in [8, 24, 64, 128, 200, 520, 576, 1000, 1088, 1536, 1560, 1600, 2048, 4096, 8200, 16384]:
         gps = 37 if group <= 2048 else 5
         for bits, rounding in [(4, W.NEAREST), (2, W.STOCHASTIC), (3, W.NEAREST), (6, W.STOCHASTIC), (8, W.NEAREST),
                                (2, W.NEAREST)]:

@@ -87,7 +87,8 @@ def _run(H, dtype, group, keep, n_groups, kind, rounding=0, seed=1, batch=1):
 
 SHAPES = [(8, 1), (8, 8), (64, 13), (128, 26), (512, 112), (520, 104), (1024, 208), (1600, 320), (2048, 411),
           (1600, 1), (1600, 1599), (1600, 1600), (2048, 1), (2048, 2048),    # nothing but the largest; (nearly) everything
-          (1544, 7), (1560, 300), (576, 100), (1592, 1591)]                  # a last round of 1, 3, 8 and 7 chunks
+          (1544, 7), (1560, 300), (576, 100), (1592, 1591),                  # a last round of 1, 3, 8 and 7 chunks
+          (1536, 307), (1088, 217)]                                          # three rounds; two rounds and eight chunks
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
