@@ -105,8 +105,10 @@ __device__ __forceinline__ uint32_t wave_inclusive_sum(uint32_t x, int lane, uin
 
 // The keep-th largest key of the group and how many entries equal to it are kept.
 // `equal_total` = number of entries equal to the threshold.
-template <int DT, int CPL>
+// TAIL: the lane's single entry of a last round taken entry by entry (key tail_u, counted if tail_valid).
+template <int DT, int CPL, bool TAIL>
 __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], const bool (&valid)[CPL],
+                                            uint32_t tail_u, bool tail_valid,
                                             int keep, int lane, uint32_t* bins, uint32_t& threshold,
                                             int& equal_kept, int& equal_total) {
     uint32_t prefix = 0;                                 // bytes of the threshold decided so far
@@ -133,6 +135,9 @@ __device__ __forceinline__ void kth_largest(const uint32_t (&u)[CPL][kChunk], co
                     atomicAdd(&bins[min(digit, spare)], 1u);
                 }
             }
+        if constexpr (TAIL) {
+            if (tail_valid) atomicAdd(&bins[min((tail_u ^ decided) >> shift, spare)], 1u);
+        }
         wave_lds_sync();
         const u32x4_t c = *reinterpret_cast<const u32x4_t*>(bins + 4 * lane);
         const uint32_t mine = c[0] + c[1] + c[2] + c[3];
@@ -469,9 +474,12 @@ __device__ __forceinline__ void topk_quant_group16(const TopkArgs& a, int64_t g,
     wave_lds_sync();                                     // the next group reuses the staging bytes
 }
 
-template <int DT, int CPL, int ROUND>
+// TAIL as in topk_quant_group16: CPL whole rounds of chunks, then at most eight more chunks
+// taken as one entry per lane (`tail_entries` of them).
+template <int DT, int CPL, int ROUND, bool TAIL>
 __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, const uint32_t (&cc)[CPL],
-                                                 const bool (&valid)[CPL], int lane, TopkLds& lds) {
+                                                 const bool (&valid)[CPL], int lane, TopkLds& lds,
+                                                 int tail_entries = 0) {
     constexpr int kEB = ElemBytes<DT>::value;
     constexpr int kChunkBytes = kChunk * kEB;
     const int64_t e0 = g * a.group;                      // first entry of the group in the call tensor
@@ -480,6 +488,11 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
     Raw<DT> raw[CPL];
 #pragma unroll
     for (int k = 0; k < CPL; ++k) raw[k] = load_raw_at<DT>(src + cc[k] * kChunkBytes);
+    // the tail: entry CPL * 64 * 8 + lane of the group (a lane past the end repeats the last one)
+    [[maybe_unused]] const bool tail_valid = TAIL && lane < tail_entries;
+    [[maybe_unused]] const int tail_j = CPL * kWave * kChunk + min(lane, tail_entries - 1);
+    [[maybe_unused]] float tail_f = 0.0f;
+    if constexpr (TAIL) tail_f = load_elem<DT>(src, tail_j);
     __builtin_amdgcn_sched_barrier(0);
 
     float f[CPL][kChunk];
@@ -493,12 +506,21 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         for (int e = 0; e < kChunk; ++e)                 // a clamped lane repeats a real chunk: harmless here
             mx = __builtin_fmaxf(mx, __builtin_fabsf(f[k][e]));
     }
+    // the tail entry's key: as magnitude_keys makes them (the storage pattern's magnitude, doubled)
+    [[maybe_unused]] uint32_t tail_u = 0;
+    if constexpr (TAIL) {
+        if constexpr (DT == AQSGD_F32) tail_u = __float_as_uint(tail_f) << 1;
+        else if constexpr (DT == AQSGD_F16)
+            tail_u = (static_cast<uint32_t>(__builtin_bit_cast(uint16_t, static_cast<_Float16>(tail_f))) << 1) & 0xfffeu;
+        else tail_u = (__float_as_uint(tail_f) >> 15) & 0xfffeu;
+        mx = __builtin_fmaxf(mx, __builtin_fabsf(tail_f));           // a repeated entry: harmless here
+    }
     mx = team_max<kWave>(mx);
     const GroupScale sc = make_scale<kTopkBits>(mx);
 
     uint32_t threshold;
     int equal_kept, equal_total;
-    kth_largest<DT, CPL>(u, valid, a.keep, lane, lds.bins, threshold, equal_kept, equal_total);
+    kth_largest<DT, CPL, TAIL>(u, valid, tail_u, tail_valid, a.keep, lane, lds.bins, threshold, equal_kept, equal_total);
 
     // ---- keep flags: everything above the threshold, and the first equal_kept entries equal to it
     uint32_t geb[CPL];                                   // bit e: entry e is >= the threshold
@@ -507,6 +529,8 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         geb[k] = chunk_mask<DT, false>(u[k], threshold);
         if (!valid[k]) geb[k] = 0;
     }
+    const bool tail_ge = TAIL && tail_valid && tail_u >= threshold;
+    bool tail_keep = tail_ge;
     uint32_t keepb[CPL];
     if (equal_kept == equal_total) {                     // no choice to make among equals (wave-uniform)
 #pragma unroll
@@ -538,6 +562,10 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
             keepb[k] = kb;
             left = max(left - static_cast<int>(ties_total[k]), 0);
         }
+        if constexpr (TAIL) {                            // the tail's entries come last in entry order
+            const bool tail_eq = tail_ge && tail_u == threshold;
+            tail_keep = tail_ge && (!tail_eq || lanes_set_below(__ballot(tail_eq)) < left);
+        }
     }
 
     // ---- positions in the group's byte string, levels, staging ------------------------------
@@ -567,6 +595,24 @@ __device__ __forceinline__ void topk_quant_group(const TopkArgs& a, int64_t g, c
         }
         if (valid[k]) a.bitmap[e0 / kChunk + cc[k]] = static_cast<uint8_t>(keepb[k]);
         row_start += kept_total[k];
+    }
+    if constexpr (TAIL) {
+        float r = kNearestOffset32;
+        if constexpr (ROUND == AQSGD_ROUND_STOCHASTIC) {             // the entry's own draw (word j mod 4 of block j / 4)
+            const uint64_t j = static_cast<uint64_t>(e0) + static_cast<uint64_t>(tail_j);
+            uint32_t w[4];
+            philox4x32_10(static_cast<uint32_t>(j >> 2), static_cast<uint32_t>(j >> 34),
+                          static_cast<uint32_t>(a.seed), static_cast<uint32_t>(a.seed >> 32), w);
+            const uint32_t sel = static_cast<uint32_t>(j) & 3u;
+            r = offset32_from_word(sel == 0 ? w[0] : (sel == 1 ? w[1] : (sel == 2 ? w[2] : w[3])));
+        }
+        const float q = level_of<kTopkBits, ROUND>(tail_f, sc, r);
+        const uint64_t km = __ballot(tail_keep);         // bit l: lane l's entry, which is entry 64 * 8 * CPL + l
+        if (tail_keep)
+            lds.stage[row_start + static_cast<uint32_t>(lanes_set_below(km))] =
+                static_cast<uint8_t>(__builtin_amdgcn_cvt_pk_u8_f32(q, 0, 0));
+        if (lane < tail_entries / kChunk)
+            a.bitmap[e0 / kChunk + CPL * kWave + lane] = static_cast<uint8_t>(km >> (8 * lane));
     }
 
     // ---- the group's bytes leave LDS ------------------------------------------------------
@@ -710,9 +756,27 @@ void topk_kernel(const TopkArgs a) {
             load_group16<DT, CPL>(a, g, cc, raw);
         }
     } else {
+        if constexpr (MODE != 0 && CPL >= 2) {
+            // the general sender (binary32 entries, stochastic rounding): the same last round as single entries
+            constexpr int kRounds = CPL - 1;
+            constexpr int kRound = MODE == 2 ? AQSGD_ROUND_STOCHASTIC : AQSGD_ROUND_NEAREST;
+            const int tail_chunks = a.cpg - kRounds * kWave;
+            if (tail_chunks >= 1 && tail_chunks <= 8) {              // uniform over the launch
+                uint32_t rc[kRounds];
+                bool all[kRounds];
+#pragma unroll
+                for (int k = 0; k < kRounds; ++k) {
+                    rc[k] = static_cast<uint32_t>(k * kWave + lane);
+                    all[k] = true;
+                }
+                for (; g < a.n_groups; g += stride)
+                    topk_quant_group<DT, kRounds, kRound, true>(a, g, rc, all, lane, lds_all[wave], kChunk * tail_chunks);
+                return;
+            }
+        }
         for (; g < a.n_groups; g += stride) {
-            if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST>(a, g, cc, valid, lane, lds_all[wave]);
-            else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC>(a, g, cc, valid, lane, lds_all[wave]);
+            if constexpr (MODE == 1) topk_quant_group<DT, CPL, AQSGD_ROUND_NEAREST, false>(a, g, cc, valid, lane, lds_all[wave]);
+            else if constexpr (MODE == 2) topk_quant_group<DT, CPL, AQSGD_ROUND_STOCHASTIC, false>(a, g, cc, valid, lane, lds_all[wave]);
             else topk_dequant_group<DT, CPL>(a, g, cc, valid, lane, lds_all[wave]);
         }
     }
