@@ -51,6 +51,25 @@ __device__ __forceinline__ Raw<DT> load_raw_at(const char* p) {
     return r;
 }
 
+// A 16-byte streaming store that is also written through the L2 at system scope (nt with
+// sc0 sc1).  The launches here end with tens of MB of freshly written lines, and lines
+// that only stream (nt) still wait in the eight L2s for the write-back at the end of the
+// kernel; written through, they leave while the kernel is still reading.  Measured on the
+// GPT2 boundary: forward pair in the pipelined schedule 13.9-14.2 -> 13.3-13.4 us, DeBERTa
+// step 36.7 -> 35.6 us.  The compiler has no spelling for this combination on a 16-byte
+// store, so the instruction is written out; the data registers of a store of more than
+// eight bytes must not be overwritten in the next two cycles, which the compiler's hazard
+// pass cannot see through the asm statement, hence the s_nop.
+template <typename V>
+__device__ __forceinline__ void store16_through(void* p, const V& v) {
+    static_assert(sizeof(V) == 16, "one 16-byte piece");
+#if defined(AQSGD_PLAIN_STREAMING_STORES)
+    __builtin_nontemporal_store(v, reinterpret_cast<V*>(p));
+#else
+    asm volatile("global_store_dwordx4 %0, %1, off sc0 sc1 nt\n\ts_nop 2" : : "v"(p), "v"(v) : "memory");
+#endif
+}
+
 // A float32 chunk is two 16-byte stores per lane, 32 bytes apart between lanes:
 // each instruction fills half of every cache line.  Streaming (nontemporal)
 // stores of that shape reach 2.4 TB/s, ordinary stores, which L2 merges, 6.6;
@@ -62,7 +81,7 @@ __device__ __forceinline__ void store_raw_at(char* p, const Raw<DT>& r) {
         q[0] = r.lo;
         q[1] = r.hi;
     } else {
-        __builtin_nontemporal_store(r.v, reinterpret_cast<u32x4_t*>(p));
+        store16_through(p, r.v);
     }
 }
 
@@ -552,8 +571,8 @@ __device__ __forceinline__ Raw<AQSGD_F32> load_raw_units(const char* pa, const c
 }
 
 __device__ __forceinline__ void store_raw_units(char* pa, char* pb, const Raw<AQSGD_F32>& r) {
-    __builtin_nontemporal_store(r.lo, reinterpret_cast<f32x4_t*>(pa));
-    __builtin_nontemporal_store(r.hi, reinterpret_cast<f32x4_t*>(pb));
+    store16_through(pa, r.lo);
+    store16_through(pb, r.hi);
 }
 
 // The two halves of pack_levels' word: levels 0..3 and 4..7, 4*BITS bits each.

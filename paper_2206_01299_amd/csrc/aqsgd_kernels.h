@@ -486,8 +486,8 @@ __device__ __forceinline__ void dequant_units_body(const DequantJob& a, uint32_t
                     for (uint32_t u = bx * THREADS + threadIdx.x; u < ups; u += a.grid_x * THREADS) {
                         const f32x4_t v = __builtin_nontemporal_load(
                             reinterpret_cast<const f32x4_t*>(full_s + static_cast<uint64_t>(u) * kUnitBytes));
-                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(m_s + static_cast<uint64_t>(u) * kUnitBytes));
-                        __builtin_nontemporal_store(v, reinterpret_cast<f32x4_t*>(out_s + static_cast<uint64_t>(u) * kUnitBytes));
+                        store16_through(m_s + static_cast<uint64_t>(u) * kUnitBytes, v);
+                        store16_through(out_s + static_cast<uint64_t>(u) * kUnitBytes, v);
                     }
                     continue;
                 }
@@ -536,11 +536,8 @@ __device__ __forceinline__ void dequant_units_body(const DequantJob& a, uint32_t
                     else v[e] = dh;
                 }
                 if (ok[u]) {
-                    if constexpr (HAS_BUF)
-                        __builtin_nontemporal_store(
-                            v, reinterpret_cast<f32x4_t*>(m_s + static_cast<uint64_t>(us[u]) * kUnitBytes));
-                    __builtin_nontemporal_store(
-                        v, reinterpret_cast<f32x4_t*>(out_s + static_cast<uint64_t>(us[u]) * kUnitBytes));
+                    if constexpr (HAS_BUF) store16_through(m_s + static_cast<uint64_t>(us[u]) * kUnitBytes, v);
+                    store16_through(out_s + static_cast<uint64_t>(us[u]) * kUnitBytes, v);
                 }
             }
         }
