@@ -370,7 +370,7 @@ void seed_rows_kernel(const V* act, const int64_t* ids, V* m_buf, int64_t units_
              c += static_cast<int64_t>(gridDim.x) * kBlock) {
             if constexpr (sizeof(V) == 16) {
                 const V v = __builtin_nontemporal_load(src + c);
-                __builtin_nontemporal_store(v, dst + c);
+                store16_through(dst + c, v);
             } else {
                 dst[c] = src[c];
             }
